@@ -1,0 +1,187 @@
+"""ctypes binding of the CPU oracle (test infrastructure; see iodf_oracle.h).
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+def build(force=False):
+    """Compile liboracle.so with gcc (make)."""
+    if force:
+        subprocess.check_call(["make", "-s", "-C", _HERE, "clean"])
+    subprocess.check_call(["make", "-s", "-C", _HERE])
+    return os.path.join(_HERE, "liboracle.so")
+
+
+def lib():
+    global _LIB
+    if _LIB is None:
+        path = os.path.join(_HERE, "liboracle.so")
+        src = os.path.join(_HERE, "iodf_oracle.c")
+        if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(src):
+            build()
+        L = ctypes.CDLL(path)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        ci = ctypes.c_int
+        L.orc_rq.restype = i64
+        L.orc_rq.argtypes = [i32, i32, ci]
+        L.orc_sat8.restype = i32
+        L.orc_sat8.argtypes = [i64]
+        L.orc_set_threads.argtypes = [ci]
+        L.orc_get_threads.restype = ci
+        L.orc_conv_acc.restype = None
+        L.orc_conv_acc.argtypes = [vp, ci, ci, ci, vp, ci, ci, vp, vp, vp]
+        L.orc_epilogue.restype = None
+        L.orc_epilogue.argtypes = [vp, ci, ci, vp, vp, vp, ci, vp, vp]
+        L.orc_squeeze.restype = None
+        L.orc_squeeze.argtypes = [vp, ci, ci, ci, vp]
+        L.orc_unsqueeze.restype = None
+        L.orc_unsqueeze.argtypes = [vp, ci, ci, ci, vp]
+        L.orc_model_load.restype = ci
+        L.orc_model_load.argtypes = [vp, sz, ctypes.POINTER(vp)]
+        L.orc_model_free.restype = None
+        L.orc_model_free.argtypes = [vp]
+        L.orc_model_num_nets.restype = ci
+        L.orc_model_num_nets.argtypes = [vp]
+        L.orc_model_d.restype = i64
+        L.orc_model_d.argtypes = [vp]
+        L.orc_model_d_codes.restype = i64
+        L.orc_model_d_codes.argtypes = [vp]
+        L.orc_net_eval.restype = ci
+        L.orc_net_eval.argtypes = [vp, ci, vp, ci, ci, vp]
+        L.orc_forward.restype = ci
+        L.orc_forward.argtypes = [vp, vp, ci, vp, vp]
+        L.orc_inverse.restype = ci
+        L.orc_inverse.argtypes = [vp, vp, ci, vp, ctypes.POINTER(i64)]
+        L.orc_last_max_abs_state.restype = i64
+        _LIB = L
+    return _LIB
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def rq(a, M, s):
+    return int(lib().orc_rq(int(a), int(M), int(s)))
+
+
+def sat8(u):
+    return int(lib().orc_sat8(int(u)))
+
+
+def set_threads(n):
+    lib().orc_set_threads(int(n))
+
+
+def get_threads():
+    return int(lib().orc_get_threads())
+
+
+def conv_acc(x, W, bias=None, gate=None):
+    """x int8 [D,h,w], W int8 [C,D,k,k] -> int32 accumulators [C,h,w] (Eq. 4)."""
+    x = np.ascontiguousarray(x, dtype=np.int8)
+    W = np.ascontiguousarray(W, dtype=np.int8)
+    D, h, w = x.shape
+    C, D2, k, k2 = W.shape
+    assert D == D2 and k == k2
+    bias = None if bias is None else np.ascontiguousarray(bias, dtype=np.int32)
+    gate = None if gate is None else np.ascontiguousarray(gate, dtype=np.uint8)
+    acc = np.zeros((C, h, w), dtype=np.int32)
+    lib().orc_conv_acc(_p(x), D, h, w, _p(W), C, k, _p(bias), _p(gate), _p(acc))
+    return acc
+
+
+def epilogue(acc, M, shift, gate=None, relu=False, shortcut=None):
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    C = acc.shape[0]
+    hw = int(np.prod(acc.shape[1:]))
+    M = np.ascontiguousarray(M, dtype=np.int32)
+    shift = np.ascontiguousarray(shift, dtype=np.uint8)
+    gate = None if gate is None else np.ascontiguousarray(gate, dtype=np.uint8)
+    shortcut = None if shortcut is None else np.ascontiguousarray(shortcut, dtype=np.int8)
+    y = np.zeros(acc.shape, dtype=np.int8)
+    lib().orc_epilogue(_p(acc), C, hw, _p(M), _p(shift), _p(gate), int(relu), _p(shortcut), _p(y))
+    return y
+
+
+def squeeze(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    C, H, W = a.shape
+    out = np.zeros((4 * C, H // 2, W // 2), dtype=np.int32)
+    lib().orc_squeeze(_p(a), C, H, W, _p(out))
+    return out
+
+
+def unsqueeze(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    C4, h, w = a.shape
+    out = np.zeros((C4 // 4, 2 * h, 2 * w), dtype=np.int32)
+    lib().orc_unsqueeze(_p(a), C4 // 4, 2 * h, 2 * w, _p(out))
+    return out
+
+
+class Model:
+    """A loaded model blob."""
+
+    _h = None
+
+    def __init__(self, blob):
+        blob = np.ascontiguousarray(blob, dtype=np.uint8)
+        h = ctypes.c_void_p()
+        rc = lib().orc_model_load(_p(blob), blob.size, ctypes.byref(h))
+        if rc != 0:
+            raise ValueError("oracle: bad model blob (code %d)" % rc)
+        self._h = h
+        self.d = int(lib().orc_model_d(h))
+        self.d_codes = int(lib().orc_model_d_codes(h))
+        self.n_nets = int(lib().orc_model_num_nets(h))
+
+    def close(self):
+        if self._h:
+            lib().orc_model_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    def net_eval(self, net, xa, c_out):
+        xa = np.ascontiguousarray(xa, dtype=np.int32)
+        _, h, w = xa.shape
+        out = np.zeros((c_out, h, w), dtype=np.int8)
+        rc = lib().orc_net_eval(self._h, net, _p(xa), h, w, _p(out))
+        if rc != 0:
+            raise RuntimeError("oracle net_eval failed (%d)" % rc)
+        return out
+
+    def forward(self, x):
+        x = np.ascontiguousarray(x, dtype=np.uint8)
+        b = x.shape[0]
+        assert x.size == b * self.d
+        z = np.zeros((b, self.d), dtype=np.int32)
+        codes = np.zeros((b, self.d_codes), dtype=np.int8)
+        rc = lib().orc_forward(self._h, _p(x), b, _p(z), _p(codes) if self.d_codes else None)
+        if rc != 0:
+            raise RuntimeError("oracle forward failed (%d)" % rc)
+        return z, codes
+
+    def inverse(self, z, shape):
+        z = np.ascontiguousarray(z, dtype=np.int32)
+        b = z.shape[0]
+        x = np.zeros((b,) + tuple(shape), dtype=np.uint8)
+        errs = ctypes.c_int64(0)
+        rc = lib().orc_inverse(self._h, _p(z), b, _p(x), ctypes.byref(errs))
+        if rc != 0:
+            raise RuntimeError("oracle inverse failed (%d)" % rc)
+        return x, int(errs.value)
+
+    @staticmethod
+    def last_max_abs_state():
+        return int(lib().orc_last_max_abs_state())
