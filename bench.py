@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Benchmark of the integer-only flow's hot path on one MI355X.
+
+A step is one pass of the whole encode path (ingest, squeeze, every coupling
+network, factor-out, prior heads) over one batch of seeded synthetic images that
+are already resident in HBM. Prints ONE JSON line (see the keys below).
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg4] [--direction forward|inverse]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA peak, TOP/s
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="cfg4")
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--direction", default="forward", choices=["forward", "inverse"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (images are independent; a multi-GPU run would "
+              "only shard the batch). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2206_08869_amd as iodf
+    from synth import CONFIGS, make_blob, make_images
+
+    cfg = CONFIGS[args.config]
+    batch = args.batch or cfg.batch
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU (no CPU fallback exists)")
+    iodf.load_library()
+
+    t0 = time.time()
+    blob = make_blob(cfg)
+    x_host = make_images(cfg, batch=batch)
+    t_gen = time.time() - t0
+    t0 = time.time()
+    flow = iodf.Flow(blob, max_batch=batch, device=0)
+    t_init = time.time() - t0
+    x = torch.from_numpy(x_host).cuda()
+    z = torch.empty((batch, flow.d), dtype=torch.int32, device="cuda")
+    codes = torch.empty((batch, max(flow.d_codes, 1)), dtype=torch.int8, device="cuda")
+    x_out = torch.empty_like(x)
+    macs_img = flow.query(iodf.IODF_Q_MACS_FORWARD if args.direction == "forward" else iodf.IODF_Q_MACS_INVERSE)
+    launches = flow.query(iodf.IODF_Q_CONV_LAUNCHES)
+
+    def step():
+        if args.direction == "forward":
+            flow.forward(x, z=z, codes=codes if flow.d_codes else None)
+        else:
+            flow.inverse(z, x=x_out)
+
+    if args.direction == "inverse":
+        flow.forward(x, z=z, codes=codes if flow.d_codes else None)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    if not args.no_profile:
+        flow.profile_begin(args.steps * (2 * launches + 256))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    stats = [] if args.no_profile else flow.profile_end()
+
+    # validity: the timed outputs decode back to the inputs exactly
+    if args.direction == "forward":
+        flow.inverse(z, x=x_out)
+    torch.cuda.synchronize()
+    round_trip = bool(torch.equal(x_out, x)) and flow.range_errors() == 0
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = batch * args.steps / elapsed
+    whole_tops = 2.0 * macs_img * value / 1e12
+
+    roofline = None
+    kernels = []
+    if stats:
+        for s in stats:
+            avg_ms = s["total_ms"] / s["launches"]
+            k = dict(name=s["name"], launches=s["launches"], total_ms=round(s["total_ms"], 3),
+                     avg_ms=round(avg_ms, 5))
+            if s["macs"]:
+                k["tops"] = round(2.0 * s["macs"] / (s["total_ms"] * 1e-3) / 1e12, 2)
+            k["alg_gbs"] = round(s["bytes"] / (s["total_ms"] * 1e-3) / 1e9, 1)
+            kernels.append(k)
+        dom = max((s for s in stats if s["macs"]), key=lambda s: s["total_ms"])
+        achieved = 2.0 * dom["macs"] / (dom["total_ms"] * 1e-3) / 1e12
+        roofline = dict(bound="mfma", kernel=dom["name"], achieved=round(achieved, 2), peak=INT8_PEAK_TOPS,
+                        unit="TOP/s", frac=round(achieved / INT8_PEAK_TOPS, 4), traffic=None,
+                        launches=dom["launches"], avg_launch_ms=round(dom["total_ms"] / dom["launches"], 5),
+                        share_of_step=round(dom["total_ms"] / (1e3 * elapsed), 4))
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        om = oracle.Model(blob)
+        n_img = 1 if macs_img > 5e10 else min(batch, max(1, int(2e11 // max(macs_img, 1))))
+        t0 = time.perf_counter()
+        if args.direction == "forward":
+            z_ref, c_ref = om.forward(x_host[:n_img])
+        else:
+            z_ref, c_ref = om.forward(x_host[:n_img])
+            t0 = time.perf_counter()
+            om.inverse(z_ref, x_host.shape[1:])
+        dt = time.perf_counter() - t0
+        same = bool(np.array_equal(z[:n_img].cpu().numpy(), z_ref))
+        cpu = dict(value=round(n_img / dt, 4), unit="images/s", cores=oracle.get_threads(), kind="oracle",
+                   sample="%d image(s) of the same batch, %s, %.1f s" % (n_img, args.direction, dt),
+                   matches_gpu=same)
+
+    out = {
+        "metric": "encode-inference images/sec at 3x%dx%d" % (cfg.H, cfg.W) if args.direction == "forward"
+        else "decode-inference images/sec at 3x%dx%d" % (cfg.H, cfg.W),
+        "value": round(value, 2), "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "%s: %d x 3x%dx%d u8 filtered-noise images, %d levels x %d couplings, %s t() width %d "
+                               "depth %d, keep %.2f, prior heads %s; %s" %
+                               (cfg.name, batch, cfg.H, cfg.W, cfg.levels, cfg.couplings,
+                                ["plain", "residual", "dense"][cfg.family], cfg.width, cfg.depth, cfg.keep,
+                                "on" if cfg.heads else "off", args.direction),
+                   "batch": batch, "macs_per_image": macs_img},
+        "whole_path_tops": round(whole_tops, 2),
+        "whole_path_frac_of_int8_peak": round(whole_tops / INT8_PEAK_TOPS, 4),
+        "round_trip_exact": round_trip,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels": kernels,
+        "setup_s": {"generate": round(t_gen, 1), "init": round(t_init, 1)},
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,136 @@
+/*
+ * libiodf: integer-only inference of an Integer-only Discrete Flow (arXiv
+ * 2206.08869) on AMD MI355X (gfx950). C ABI: plain pointers and sizes only.
+ *
+ * The flow maps an image x in Z^d to a latent z = f(x) of the same size and back
+ * (Sec. 3). f is a stack of levels; each level squeezes space to depth, applies K
+ * additive couplings  z_a = x_a, z_b = x_b + t(x_a)  (Sec. 3, Eq. 1) and factors
+ * half of the channels out. t() is an integer-only network: 8-bit codes, int8 x
+ * int8 convolutions with 32-bit accumulator and bias, a per-channel fixed-point
+ * rescale back to 8 bit, integer ReLU (Sec. 4.1, Eq. 2-5), with gated-off filters
+ * physically removed and residual sums done by scatter-add (Sec. 4.4, Eq. 8).
+ *
+ * Pointer conventions: "host" = ordinary process memory; "device" = memory of
+ * the GPU the context was created on, owned by the caller (for instance a
+ * PyTorch-ROCm tensor's data_ptr()). `stream` is a hipStream_t passed as void*
+ * (NULL = the default stream). iodf_forward / iodf_inverse only enqueue work on
+ * that stream and never synchronise; the caller synchronises before reading.
+ * A context must not be used from two streams at once (it owns one workspace).
+ *
+ * Every function returns IODF_OK (0) or a negative IODF_E_* code; nothing throws.
+ */
+#ifndef IODF_H
+#define IODF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct iodf_ctx iodf_ctx;
+
+enum {
+    IODF_OK = 0,
+    IODF_E_ARG = -1,    /* NULL or out-of-range argument */
+    IODF_E_BLOB = -2,   /* malformed model blob (magic, truncation, bad constants) */
+    IODF_E_SHAPE = -3,  /* blob is well formed but its layers do not fit the declared family */
+    IODF_E_BATCH = -4,  /* batch < 0 or batch > max_batch */
+    IODF_E_HIP = -5,    /* a HIP runtime call failed (iodf_last_hip_error has the code) */
+    IODF_E_NOMEM = -6   /* host or device allocation failed */
+};
+
+/* What iodf_query reports. */
+enum {
+    IODF_Q_Z_ELEMS = 0,          /* d: int32 latent elements per image (= 3*H*W) */
+    IODF_Q_CODE_BYTES = 1,       /* int8 prior-parameter codes per image (0 without heads) */
+    IODF_Q_WORKSPACE_BYTES = 2,  /* device memory held by the context */
+    IODF_Q_MACS_FORWARD = 3,     /* algorithmic multiply-accumulates per image, kept channels only, true widths */
+    IODF_Q_MACS_INVERSE = 4,     /* same for decode (no prior heads) */
+    IODF_Q_RANGE_ERRORS = 5,     /* pixels outside [0,255] met by iodf_inverse since the last query;
+                                    synchronises the device and resets the counter */
+    IODF_Q_MAX_BATCH = 6,
+    IODF_Q_IMAGE_H = 7,
+    IODF_Q_IMAGE_W = 8,
+    IODF_Q_CONV_LAUNCHES = 9,    /* convolution kernels per forward call */
+    IODF_Q_WIDE_MACS_FORWARD = 10 /* of IODF_Q_MACS_FORWARD, the part in layers whose C_in and C_out are both >= 128 */
+};
+
+/*
+ * Build a context from a model blob (Sec. 4.1, 4.4: weights, per-channel rescale
+ * constants, binary gates).
+ *   out          host; receives the context (caller releases it with iodf_free).
+ *   model_blob   host; little-endian, 4-byte aligned fields:
+ *                  header 16 x u32: 'IODF','BLB1', version 1, H, W, levels, couplings per
+ *                    level, family (0 plain, 1 residual, 2 dense), width, depth, has_heads,
+ *                    n_nets, 4 x reserved
+ *                  per network in flow order (level 1 couplings, level 1 head, level 2, ...):
+ *                    8 x 32 bit: kind (0 coupling, 1 head), level, C_level, C_in, C_out,
+ *                    n_layers, M_in (i32), s_in; then i32 perm[C_level] for couplings;
+ *                    per conv layer: 4 x u32 C_out, C_in, k (1|3), flags (bit0 ReLU, bit1
+ *                    shortcut); i8 W[C_out][C_in][k][k]; i32 bias[C_out]; i32 M[C_out];
+ *                    u8 shift[C_out]; u8 gate[C_out] (1 = keep); arrays padded to 4 bytes.
+ *                The blob is copied/repacked; the caller may free it on return. Filters with
+ *                gate 0 and the matching input columns of their consumers are removed here,
+ *                so they cost nothing at inference.
+ *   device_ordinal  HIP device to run on.
+ *   max_batch    largest batch later calls may pass (sizes the workspace); >= 1.
+ * Constants must satisfy 0 <= M < 2^31, 0 <= shift <= 62, |bias| < 2^30.
+ */
+int iodf_init(iodf_ctx** out, const void* model_blob, size_t blob_bytes, int device_ordinal, int max_batch);
+
+/*
+ * Encode (Sec. 3: z = f(x)).
+ *   x_dev      device, uint8 [batch][3][H][W]; read only.
+ *   z_dev      device, int32 [batch][d]; per image the concatenation over levels l = 1..L of
+ *              the factored-out chunk [C_z,l][h_l][w_l] (last level: all channels).
+ *   codes_dev  device, int8 [batch][code bytes], or NULL to skip the prior heads; per image
+ *              the concatenation over heads l = 1..L-1 of [2*C_z,l][h_l][w_l]: first C_z,l maps
+ *              are the codes of the logistic prior's mean, the rest of its log-scale (Sec. 3).
+ * batch may be 0 (no work).
+ */
+int iodf_forward(iodf_ctx* ctx, const uint8_t* x_dev, int batch, int32_t* z_dev, int8_t* codes_dev, void* stream);
+
+/*
+ * Decode (Sec. 3: x = f^{-1}(z)): couplings replayed in reverse, x_b = z_b - t(z_a).
+ *   z_dev  device, int32 [batch][d], layout as written by iodf_forward; read only.
+ *   x_dev  device, uint8 [batch][3][H][W]. A z that is no image of any x can decode to a
+ *          value outside [0,255]: the byte is saturated and counted (IODF_Q_RANGE_ERRORS).
+ */
+int iodf_inverse(iodf_ctx* ctx, const int32_t* z_dev, int batch, uint8_t* x_dev, void* stream);
+
+/*
+ * Per-kernel timing for roofline reports (the paper reports latency only, Sec. 5.2; this is
+ * measurement support, not part of the method). Between begin and end every kernel launch of
+ * iodf_forward / iodf_inverse is bracketed by HIP events on the caller's stream (no
+ * synchronisation is added). max_launches bounds the launches recorded; later ones run untimed.
+ * iodf_profile_end waits for the recorded work, then fills stats (host, caller-owned, up to
+ * max_stats entries, one per kernel that ran) and *n_stats.
+ */
+typedef struct iodf_kernel_stat {
+    char name[48];      /* kernel, e.g. "conv_igemm<256,256,2,2>" or "k_quant_in" */
+    int64_t launches;
+    double total_ms;    /* sum of event-measured durations */
+    int64_t macs;       /* algorithmic multiply-accumulates of those launches (kept channels, true widths) */
+    int64_t bytes;      /* algorithmic bytes: live inputs + outputs (+ weights) read or written once */
+} iodf_kernel_stat;
+int iodf_profile_begin(iodf_ctx* ctx, int max_launches);
+int iodf_profile_end(iodf_ctx* ctx, iodf_kernel_stat* stats, int max_stats, int* n_stats);
+
+/* Read one IODF_Q_* quantity into *out (host). */
+int iodf_query(iodf_ctx* ctx, int what, int64_t* out);
+
+/* Release the context and its device memory. NULL is ignored. */
+void iodf_free(iodf_ctx* ctx);
+
+/* Static, NUL-terminated description of an IODF_E_* code. */
+const char* iodf_strerror(int code);
+
+/* The hipError_t value behind the most recent IODF_E_HIP on this thread (0 if none). */
+int iodf_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,11 @@
+"""MI355X-native integer-only discrete-flow inference (arXiv 2206.08869).
+
+Python surface = the C ABI of libiodf (include/iodf.h) plus a small convenience
+class. Importing the package does not load the library; the first call does, and
+raises if it has not been built.
+"""
+from .binding import (Flow, IodfError, build_library, load_library, iodf_init, iodf_forward, iodf_inverse,
+                      iodf_query, iodf_free, iodf_profile_begin, iodf_profile_end, EXPORTS, LIB_PATH,
+                      IODF_Q_Z_ELEMS, IODF_Q_CODE_BYTES, IODF_Q_WORKSPACE_BYTES, IODF_Q_MACS_FORWARD,
+                      IODF_Q_MACS_INVERSE, IODF_Q_RANGE_ERRORS, IODF_Q_MAX_BATCH, IODF_Q_IMAGE_H, IODF_Q_IMAGE_W,
+                      IODF_Q_CONV_LAUNCHES, IODF_Q_WIDE_MACS_FORWARD)

@@ -1,0 +1,199 @@
+"""Thin ctypes binding of libiodf (argument marshalling only).
+
+Function names mirror the C ABI in include/iodf.h. PyTorch supplies device memory
+(tensor.data_ptr()) and the stream; every step of the flow runs in the library's
+HIP kernels. There is no CPU fallback: without the built library, calls raise.
+"""
+import ctypes
+import glob
+import os
+import subprocess
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_PKG)
+LIB_PATH = os.path.join(_PKG, "libiodf.so")
+_LIB = None
+
+IODF_Q_Z_ELEMS, IODF_Q_CODE_BYTES, IODF_Q_WORKSPACE_BYTES, IODF_Q_MACS_FORWARD, IODF_Q_MACS_INVERSE, \
+    IODF_Q_RANGE_ERRORS, IODF_Q_MAX_BATCH, IODF_Q_IMAGE_H, IODF_Q_IMAGE_W, IODF_Q_CONV_LAUNCHES, \
+    IODF_Q_WIDE_MACS_FORWARD = range(11)
+
+EXPORTS = ["iodf_init", "iodf_forward", "iodf_inverse", "iodf_query", "iodf_free", "iodf_strerror",
+           "iodf_last_hip_error", "iodf_profile_begin", "iodf_profile_end"]
+
+
+class KernelStat(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 48), ("launches", ctypes.c_int64), ("total_ms", ctypes.c_double),
+                ("macs", ctypes.c_int64), ("bytes", ctypes.c_int64)]
+
+
+class IodfError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("libiodf: %s (code %d)" % (msg, code))
+        self.code = code
+
+
+def build_library(verbose=False):
+    """Compile the HIP sources for gfx950 into libiodf.so (in tree)."""
+    srcs = sorted(glob.glob(os.path.join(_PKG, "csrc", "*.hip")))
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-I", os.path.join(_ROOT, "include"), "-o", LIB_PATH] + srcs
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + out)
+    if verbose and out.strip():
+        print(out)
+    global _LIB
+    _LIB = None
+    return LIB_PATH
+
+
+def load_library(build_if_missing=True):
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    if not os.path.exists(LIB_PATH):
+        if not build_if_missing:
+            raise RuntimeError("libiodf.so is not built (run __graft_entry__.build())")
+        build_library()
+    L = ctypes.CDLL(LIB_PATH)
+    vp, ci = ctypes.c_void_p, ctypes.c_int
+    L.iodf_init.restype = ci
+    L.iodf_init.argtypes = [ctypes.POINTER(vp), vp, ctypes.c_size_t, ci, ci]
+    L.iodf_forward.restype = ci
+    L.iodf_forward.argtypes = [vp, vp, ci, vp, vp, vp]
+    L.iodf_inverse.restype = ci
+    L.iodf_inverse.argtypes = [vp, vp, ci, vp, vp]
+    L.iodf_query.restype = ci
+    L.iodf_query.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_int64)]
+    L.iodf_free.restype = None
+    L.iodf_free.argtypes = [vp]
+    L.iodf_strerror.restype = ctypes.c_char_p
+    L.iodf_strerror.argtypes = [ci]
+    L.iodf_last_hip_error.restype = ci
+    L.iodf_profile_begin.restype = ci
+    L.iodf_profile_begin.argtypes = [vp, ci]
+    L.iodf_profile_end.restype = ci
+    L.iodf_profile_end.argtypes = [vp, ctypes.POINTER(KernelStat), ci, ctypes.POINTER(ci)]
+    _LIB = L
+    return L
+
+
+def _check(rc):
+    if rc != 0:
+        L = load_library()
+        msg = L.iodf_strerror(rc).decode()
+        if rc == -5:
+            msg += " (hipError %d)" % L.iodf_last_hip_error()
+        raise IodfError(rc, msg)
+
+
+def iodf_init(blob, device_ordinal=0, max_batch=1):
+    """blob: host bytes (numpy uint8 array). Returns an opaque context handle."""
+    L = load_library()
+    blob = np.ascontiguousarray(blob, dtype=np.uint8)
+    h = ctypes.c_void_p()
+    _check(L.iodf_init(ctypes.byref(h), blob.ctypes.data_as(ctypes.c_void_p), blob.size, int(device_ordinal),
+                       int(max_batch)))
+    return h
+
+
+def iodf_forward(ctx, x_ptr, batch, z_ptr, codes_ptr, stream):
+    _check(load_library().iodf_forward(ctx, x_ptr, int(batch), z_ptr, codes_ptr, stream))
+
+
+def iodf_inverse(ctx, z_ptr, batch, x_ptr, stream):
+    _check(load_library().iodf_inverse(ctx, z_ptr, int(batch), x_ptr, stream))
+
+
+def iodf_query(ctx, what):
+    v = ctypes.c_int64(0)
+    _check(load_library().iodf_query(ctx, int(what), ctypes.byref(v)))
+    return int(v.value)
+
+
+def iodf_profile_begin(ctx, max_launches):
+    _check(load_library().iodf_profile_begin(ctx, int(max_launches)))
+
+
+def iodf_profile_end(ctx):
+    """List of dicts, one per kernel that ran since iodf_profile_begin."""
+    arr = (KernelStat * 32)()
+    n = ctypes.c_int(0)
+    _check(load_library().iodf_profile_end(ctx, arr, 32, ctypes.byref(n)))
+    return [dict(name=arr[i].name.decode(), launches=int(arr[i].launches), total_ms=float(arr[i].total_ms),
+                 macs=int(arr[i].macs), bytes=int(arr[i].bytes)) for i in range(n.value)]
+
+
+def iodf_free(ctx):
+    if ctx:
+        load_library().iodf_free(ctx)
+
+
+class Flow:
+    """A model on one GPU. Tensors in and out are torch CUDA tensors."""
+
+    def __init__(self, blob, max_batch, device=0):
+        import torch
+        self._torch = torch
+        self.device = torch.device("cuda", device)
+        self._ctx = iodf_init(blob, device, max_batch)
+        self.max_batch = max_batch
+        self.d = iodf_query(self._ctx, IODF_Q_Z_ELEMS)
+        self.d_codes = iodf_query(self._ctx, IODF_Q_CODE_BYTES)
+        self.H = iodf_query(self._ctx, IODF_Q_IMAGE_H)
+        self.W = iodf_query(self._ctx, IODF_Q_IMAGE_W)
+
+    def query(self, what):
+        return iodf_query(self._ctx, what)
+
+    def _stream(self):
+        return ctypes.c_void_p(self._torch.cuda.current_stream(self.device).cuda_stream)
+
+    def forward(self, x, want_codes=True, z=None, codes=None):
+        torch = self._torch
+        assert x.is_cuda and x.dtype == torch.uint8 and x.is_contiguous()
+        b = x.shape[0]
+        assert x.numel() == b * self.d
+        if z is None:
+            z = torch.empty((b, self.d), dtype=torch.int32, device=self.device)
+        if want_codes and self.d_codes and codes is None:
+            codes = torch.empty((b, self.d_codes), dtype=torch.int8, device=self.device)
+        cp = ctypes.c_void_p(codes.data_ptr()) if (want_codes and codes is not None and b) else None
+        iodf_forward(self._ctx, ctypes.c_void_p(x.data_ptr()) if b else None, b,
+                     ctypes.c_void_p(z.data_ptr()) if b else None, cp, self._stream())
+        return z, codes
+
+    def inverse(self, z, x=None):
+        torch = self._torch
+        assert z.is_cuda and z.dtype == torch.int32 and z.is_contiguous()
+        b = z.shape[0]
+        if x is None:
+            x = torch.empty((b, 3, self.H, self.W), dtype=torch.uint8, device=self.device)
+        iodf_inverse(self._ctx, ctypes.c_void_p(z.data_ptr()) if b else None, b,
+                     ctypes.c_void_p(x.data_ptr()) if b else None, self._stream())
+        return x
+
+    def profile_begin(self, max_launches):
+        iodf_profile_begin(self._ctx, max_launches)
+
+    def profile_end(self):
+        return iodf_profile_end(self._ctx)
+
+    def range_errors(self):
+        return iodf_query(self._ctx, IODF_Q_RANGE_ERRORS)
+
+    def close(self):
+        if getattr(self, "_ctx", None):
+            iodf_free(self._ctx)
+            self._ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

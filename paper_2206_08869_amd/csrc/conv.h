@@ -1,0 +1,61 @@
+// Launch description of one integer-only convolution layer (Sec. 4.1, Eq. 4-5)
+// as an implicit GEMM on the int8 matrix cores of gfx950.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace iodf {
+
+enum ConvMode : int {
+    MODE_ACT = 0,     // write 8-bit codes, pixel-major (NHWC), optionally + shortcut, ReLU
+    MODE_COUPLE = 1,  // last layer of t(): state[b-half] += sign * sat8(rq(acc))   (Eq. 1)
+    MODE_CODES = 2    // last layer of a prior head: write int8 codes channel-first
+};
+
+struct ConvArgs {
+    // input activations: int8, pixel-major; pixel p, channel c at in[p * in_stride + in_off + c]
+    const int8_t* in;
+    int in_stride;
+    int in_off;
+    int cin_pad;   // channels read per tap, multiple of 64 (padding columns have zero weights)
+    int taps;      // 1 (1x1) or 9 (3x3, pad 1, stride 1)
+    int h, w;      // feature map size
+    int npix;      // batch * h * w
+    // weights: int8 [n_pad][taps][cin_pad], output channel major, K contiguous
+    const int8_t* wgt;
+    int n_pad;     // multiple of 64; rows n >= true C_out are zero
+    // per output channel constants, length n_pad
+    const int32_t* bias;
+    const int32_t* mul;
+    const int32_t* shift;
+    int n_store;   // channels written (<= n_pad); multiple of 4 in MODE_ACT without out_map
+    int mode;
+    int relu;
+    // MODE_ACT
+    int8_t* out;
+    int out_stride;
+    int out_off;
+    const int32_t* out_map;  // optional: output channel n is stored at channel out_map[n] (scatter-add)
+    int shortcut;            // add the 8-bit code already stored at the output location
+    // MODE_COUPLE
+    int32_t* state;          // int32 pixel-major [npix][state_c]
+    int state_c;
+    const int32_t* idx_b;    // physical channel of translation channel n
+    int sign;                // +1 encode, -1 decode
+    // MODE_CODES
+    int8_t* codes;           // image b, channel n, pixel q at codes[b * codes_img_stride + codes_off + n * h*w + q]
+    long long codes_img_stride;
+    long long codes_off;
+};
+
+// Enqueue the layer on `stream`. Returns hipSuccess or the launch error.
+hipError_t launch_conv(const ConvArgs& a, hipStream_t stream);
+// Index of the tile configuration launch_conv picks for `a` (-1: invalid arguments),
+// the number of configurations, and a printable name ("conv_igemm<256,256,2,2>").
+int conv_pick_tile(const ConvArgs& a);
+int conv_num_tiles();
+const char* conv_tile_name(int tile);
+// One-time per-process set-up of kernel attributes (dynamic LDS sizes).
+hipError_t conv_setup();
+
+}  // namespace iodf

@@ -1,0 +1,790 @@
+// C ABI of libiodf: model-blob parsing, gate compaction and weight packing at
+// init (Sec. 4.4: gated-off filters and their consumers' input columns are removed),
+// and the encode / decode drivers that replay the couplings (Sec. 3, Eq. 1).
+#include "../../include/iodf.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "conv.h"
+#include "flow_kernels.h"
+
+using namespace iodf;
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+#define HIP_TRY(expr)                         \
+    do {                                      \
+        hipError_t e__ = (expr);              \
+        if (e__ != hipSuccess) {              \
+            g_last_hip = (int)e__;            \
+            return IODF_E_HIP;                \
+        }                                     \
+    } while (0)
+
+enum { FAM_PLAIN = 0, FAM_RESNET = 1, FAM_DENSE = 2 };
+enum { BUF_XQ = 0, BUF_A = 1, BUF_B = 2, NUM_BUFS = 3 };
+
+int round64(int n) { return (n + 63) / 64 * 64; }
+
+// ---- blob (host side view) -------------------------------------------------------
+
+struct HostLayer {
+    int C_out, C_in, k, relu, shortcut;
+    const int8_t* W;
+    const int32_t* bias;
+    const int32_t* M;
+    const uint8_t* shift;
+    const uint8_t* gate;
+};
+
+struct HostNet {
+    int kind, level, C, C_in, C_out;
+    int32_t M_in;
+    int s_in;
+    const int32_t* perm;
+    std::vector<HostLayer> layers;
+};
+
+struct HostModel {
+    int H, W, levels, couplings, family, width, depth, has_heads;
+    std::vector<HostNet> nets;
+};
+
+size_t pad4(size_t n) { return (n + 3) & ~(size_t)3; }
+
+int parse_blob(const uint8_t* p, size_t bytes, HostModel& m) {
+    if (bytes < 64 || ((uintptr_t)p & 3)) return IODF_E_BLOB;
+    const uint32_t* h = (const uint32_t*)p;
+    if (h[0] != 0x46444F49u || h[1] != 0x31424C42u || h[2] != 1u) return IODF_E_BLOB;
+    m.H = (int)h[3]; m.W = (int)h[4]; m.levels = (int)h[5]; m.couplings = (int)h[6]; m.family = (int)h[7];
+    m.width = (int)h[8]; m.depth = (int)h[9]; m.has_heads = (int)h[10];
+    const uint32_t n_nets = h[11];
+    if (m.levels < 1 || m.levels > 8 || m.couplings < 1 || m.couplings > 1024 || m.H < 2 || m.W < 2 || m.H > 8192 ||
+        m.W > 8192 || (m.H % (1 << m.levels)) || (m.W % (1 << m.levels)) || m.family < 0 || m.family > 2 ||
+        m.has_heads > 1 || m.has_heads < 0)
+        return IODF_E_BLOB;
+    const uint32_t expect = (uint32_t)(m.levels * m.couplings + (m.has_heads ? m.levels - 1 : 0));
+    if (n_nets != expect) return IODF_E_SHAPE;
+    size_t pos = 64;
+    auto need = [&](size_t n) { return pos + n <= bytes && pos + n >= pos; };
+    m.nets.resize(n_nets);
+    for (uint32_t n = 0; n < n_nets; ++n) {
+        HostNet& net = m.nets[n];
+        if (!need(32)) return IODF_E_BLOB;
+        const uint32_t* f = (const uint32_t*)(p + pos);
+        net.kind = (int)f[0]; net.level = (int)f[1]; net.C = (int)f[2]; net.C_in = (int)f[3]; net.C_out = (int)f[4];
+        const uint32_t n_layers = f[5];
+        net.M_in = (int32_t)f[6];
+        net.s_in = (int)f[7];
+        pos += 32;
+        if (net.kind < 0 || net.kind > 1 || n_layers < 2 || n_layers > 4096 || f[7] > 62 || net.M_in < 0 ||
+            net.C < 2 || net.C > 4096 || net.C_in < 1 || net.C_in > 4096 || net.C_out < 1 || net.C_out > 4096)
+            return IODF_E_BLOB;
+        net.perm = nullptr;
+        if (net.kind == 0) {
+            if (!need(4 * (size_t)net.C)) return IODF_E_BLOB;
+            net.perm = (const int32_t*)(p + pos);
+            pos += 4 * (size_t)net.C;
+            std::vector<char> seen(net.C, 0);
+            for (int c = 0; c < net.C; ++c) {
+                const int32_t pc = net.perm[c];
+                if (pc < 0 || pc >= net.C || seen[pc]) return IODF_E_BLOB;
+                seen[pc] = 1;
+            }
+        }
+        net.layers.resize(n_layers);
+        for (uint32_t l = 0; l < n_layers; ++l) {
+            HostLayer& L = net.layers[l];
+            if (!need(16)) return IODF_E_BLOB;
+            const uint32_t* g = (const uint32_t*)(p + pos);
+            pos += 16;
+            if (g[0] < 1 || g[0] > 65536 || g[1] < 1 || g[1] > 65536 || (g[2] != 1 && g[2] != 3)) return IODF_E_BLOB;
+            L.C_out = (int)g[0]; L.C_in = (int)g[1]; L.k = (int)g[2];
+            L.relu = (int)(g[3] & 1u);
+            L.shortcut = (int)((g[3] >> 1) & 1u);
+            const size_t nw = (size_t)L.C_out * L.C_in * L.k * L.k;
+            const size_t co = (size_t)L.C_out;
+            if (!need(pad4(nw))) return IODF_E_BLOB;
+            L.W = (const int8_t*)(p + pos); pos += pad4(nw);
+            if (!need(4 * co)) return IODF_E_BLOB;
+            L.bias = (const int32_t*)(p + pos); pos += 4 * co;
+            if (!need(4 * co)) return IODF_E_BLOB;
+            L.M = (const int32_t*)(p + pos); pos += 4 * co;
+            if (!need(pad4(co))) return IODF_E_BLOB;
+            L.shift = p + pos; pos += pad4(co);
+            if (!need(pad4(co))) return IODF_E_BLOB;
+            L.gate = p + pos; pos += pad4(co);
+            int kept = 0;
+            for (int c = 0; c < L.C_out; ++c) {
+                if (L.shift[c] > 62 || L.M[c] < 0 || L.gate[c] > 1) return IODF_E_BLOB;
+                if (L.bias[c] >= (1 << 30) || L.bias[c] <= -(1 << 30)) return IODF_E_BLOB;
+                kept += L.gate[c];
+            }
+            if (kept == 0) return IODF_E_BLOB;  // a layer with every filter gated off has no output at all
+        }
+    }
+    if (pos != bytes) return IODF_E_BLOB;
+    return IODF_OK;
+}
+
+int level_channels(int lv) { return 12 << (lv - 1); }
+
+// Check that the networks fit the flow structure and their family's wiring.
+int check_shapes(const HostModel& m) {
+    size_t n = 0;
+    for (int lv = 1; lv <= m.levels; ++lv) {
+        const int C = level_channels(lv);
+        for (int k = 0; k < m.couplings; ++k, ++n) {
+            const HostNet& N = m.nets[n];
+            if (N.kind != 0 || N.level != lv || N.C != C || N.C_in != C / 2 || N.C_out != C - C / 2) return IODF_E_SHAPE;
+        }
+        if (m.has_heads && lv < m.levels) {
+            const HostNet& N = m.nets[n++];
+            if (N.kind != 1 || N.level != lv || N.C != C || N.C_in != C / 2 || N.C_out != 2 * (C - C / 2))
+                return IODF_E_SHAPE;
+        }
+    }
+    for (const HostNet& N : m.nets) {
+        const std::vector<HostLayer>& L = N.layers;
+        const int nl = (int)L.size();
+        if (L[0].C_in != N.C_in || L[0].k != 3 || L[nl - 1].C_out != N.C_out || L[nl - 1].shortcut || L[0].shortcut)
+            return IODF_E_SHAPE;
+        for (int c = 0; c < N.C_out; ++c)
+            if (!L[nl - 1].gate[c]) return IODF_E_SHAPE;  // the translation / code channels cannot be gated
+        const int Wd = L[0].C_out;
+        if (m.family == FAM_PLAIN) {
+            if (nl != 2 || L[1].C_in != Wd) return IODF_E_SHAPE;
+        } else if (m.family == FAM_RESNET) {
+            if (nl % 2) return IODF_E_SHAPE;
+            for (int l = 1; l + 1 < nl; l += 2) {
+                if (L[l].C_in != Wd || L[l].shortcut || L[l + 1].C_in != L[l].C_out || L[l + 1].C_out != Wd ||
+                    !L[l + 1].shortcut)
+                    return IODF_E_SHAPE;
+            }
+            if (L[nl - 1].C_in != Wd) return IODF_E_SHAPE;
+        } else {
+            if (nl % 2) return IODF_E_SHAPE;
+            const int depth = (nl - 2) / 2;
+            for (int l = 1; l <= depth; ++l) {
+                const HostLayer &a = L[2 * l - 1], &b = L[2 * l];
+                if (a.C_in != l * Wd || a.shortcut || b.C_in != a.C_out || b.C_out != Wd || b.shortcut) return IODF_E_SHAPE;
+            }
+            if (L[nl - 1].C_in != (depth + 1) * Wd) return IODF_E_SHAPE;
+        }
+    }
+    return IODF_OK;
+}
+
+// ---- device plan -------------------------------------------------------------------
+
+struct DevLayer {
+    int taps, cin_pad, n_pad, n_store, relu, shortcut, mode;
+    int in_buf, in_off, in_stride;
+    int out_buf, out_off, out_stride;
+    size_t wgt_off, bias_off, mul_off, shift_off;  // byte offsets into the parameter arena
+    size_t map_off;                                // (size_t)-1 when there is no scatter map
+    long long macs_per_pixel;                      // algorithmic: kept rows x live columns x taps
+    long long bytes_per_pixel;                     // algorithmic: live input codes + kept output codes
+    long long wgt_bytes;                           // algorithmic: kept rows x live columns x taps
+    bool wide;
+};
+
+struct DevNet {
+    int kind, level, C, C_in, C_out, cin_pad0;
+    int32_t M_in;
+    int s_in;
+    bool zero_a;        // clear BUF_A before conv_in (scatter-written residual stream)
+    int a_stride;       // row width of BUF_A for this network (what zero_a clears)
+    size_t phi_off;     // byte offset of this coupling's composed index map (int32[C]); heads: the level's last
+    std::vector<DevLayer> layers;
+};
+
+std::vector<int> kept_rows(const HostLayer& L) {
+    std::vector<int> r;
+    for (int c = 0; c < L.C_out; ++c)
+        if (L.gate[c]) r.push_back(c);
+    return r;
+}
+
+// Packed position of every original channel of a feature tensor (-1 = removed).
+std::vector<int> rank_map(const HostLayer& producer, int base) {
+    std::vector<int> pos(producer.C_out, -1);
+    int r = 0;
+    for (int c = 0; c < producer.C_out; ++c)
+        if (producer.gate[c]) pos[c] = base + r++;
+    return pos;
+}
+
+struct Arena {
+    std::vector<uint8_t> host;
+    size_t alloc(size_t bytes) {
+        const size_t off = (host.size() + 255) & ~(size_t)255;
+        host.resize(off + bytes, 0);
+        return off;
+    }
+};
+
+// Append one layer's packed weights and constants to the arena.
+//   rows:   original output channels kept, in order
+//   colpos: packed input column of each original input channel, or -1
+void pack_layer(Arena& A, const HostLayer& L, const std::vector<int>& rows, const std::vector<int>& colpos, int cin_pad,
+                DevLayer& D) {
+    const int taps = L.k * L.k;
+    D.taps = taps;
+    D.cin_pad = cin_pad;
+    D.n_pad = round64((int)rows.size());
+    D.relu = L.relu;
+    D.shortcut = L.shortcut;
+    D.map_off = (size_t)-1;
+    const size_t wbytes = (size_t)D.n_pad * taps * cin_pad;
+    D.wgt_off = A.alloc(wbytes);
+    D.bias_off = A.alloc(4 * (size_t)D.n_pad);
+    D.mul_off = A.alloc(4 * (size_t)D.n_pad);
+    D.shift_off = A.alloc(4 * (size_t)D.n_pad);
+    int8_t* w = (int8_t*)(A.host.data() + D.wgt_off);
+    int32_t* bias = (int32_t*)(A.host.data() + D.bias_off);
+    int32_t* mul = (int32_t*)(A.host.data() + D.mul_off);
+    int32_t* sh = (int32_t*)(A.host.data() + D.shift_off);
+    int live = 0;
+    for (int c = 0; c < L.C_in; ++c) live += colpos[c] >= 0;
+    for (size_t n = 0; n < rows.size(); ++n) {
+        const int r = rows[n];
+        const int8_t* src = L.W + (size_t)r * L.C_in * taps;
+        int8_t* dst = w + n * (size_t)taps * cin_pad;
+        for (int c = 0; c < L.C_in; ++c) {
+            const int pc = colpos[c];
+            if (pc < 0) continue;
+            for (int t = 0; t < taps; ++t) dst[(size_t)t * cin_pad + pc] = src[(size_t)c * taps + t];
+        }
+        bias[n] = L.bias[r];
+        mul[n] = L.M[r];
+        sh[n] = L.shift[r];
+    }
+    D.macs_per_pixel = (long long)rows.size() * live * taps;
+    D.bytes_per_pixel = (long long)live + (long long)rows.size();
+    D.wgt_bytes = D.macs_per_pixel;
+    D.wide = rows.size() >= 128 && live >= 128;
+}
+
+size_t put_map(Arena& A, const std::vector<int>& rows, int n_pad) {
+    const size_t off = A.alloc(4 * (size_t)n_pad);
+    int32_t* m = (int32_t*)(A.host.data() + off);
+    for (size_t n = 0; n < rows.size(); ++n) m[n] = rows[n];
+    return off;
+}
+
+std::vector<int> identity_map(int n) {
+    std::vector<int> v(n);
+    for (int i = 0; i < n; ++i) v[i] = i;
+    return v;
+}
+
+// Build the launch list of one network. buf_w[b] is raised to the row width the network needs.
+void plan_net(Arena& A, const HostModel& m, const HostNet& N, DevNet& D, int buf_w[NUM_BUFS]) {
+    const std::vector<HostLayer>& L = N.layers;
+    const int nl = (int)L.size();
+    D.kind = N.kind; D.level = N.level; D.C = N.C; D.C_in = N.C_in; D.C_out = N.C_out;
+    D.M_in = N.M_in; D.s_in = N.s_in;
+    D.cin_pad0 = round64(N.C_in);
+    D.zero_a = false;
+    D.layers.resize(nl);
+    buf_w[BUF_XQ] = std::max(buf_w[BUF_XQ], D.cin_pad0);
+    const int last_mode = N.kind == 0 ? MODE_COUPLE : MODE_CODES;
+    auto io = [](DevLayer& d, int ib, int ioff, int istr, int ob, int ooff, int ostr, int mode) {
+        d.in_buf = ib; d.in_off = ioff; d.in_stride = istr;
+        d.out_buf = ob; d.out_off = ooff; d.out_stride = ostr;
+        d.mode = mode;
+    };
+    if (m.family == FAM_PLAIN) {
+        const std::vector<int> r0 = kept_rows(L[0]);
+        const int fw = round64((int)r0.size());
+        pack_layer(A, L[0], r0, identity_map(N.C_in), D.cin_pad0, D.layers[0]);
+        io(D.layers[0], BUF_XQ, 0, D.cin_pad0, BUF_A, 0, fw, MODE_ACT);
+        D.layers[0].n_store = fw;
+        pack_layer(A, L[1], kept_rows(L[1]), rank_map(L[0], 0), fw, D.layers[1]);
+        io(D.layers[1], BUF_A, 0, fw, -1, 0, 0, last_mode);
+        D.layers[1].n_store = N.C_out;
+        D.a_stride = fw;
+        buf_w[BUF_A] = std::max(buf_w[BUF_A], fw);
+    } else if (m.family == FAM_RESNET) {
+        // BUF_A: residual stream at full width; BUF_B: block-internal feature (compacted)
+        const int Wd = L[0].C_out;
+        const int rw = round64(Wd);
+        D.a_stride = rw;
+        buf_w[BUF_A] = std::max(buf_w[BUF_A], rw);
+        auto stream_out = [&](const HostLayer& H, DevLayer& d, const std::vector<int>& rows) {
+            if ((int)rows.size() == Wd) {
+                d.n_store = rw;
+            } else {  // scatter-add into the unpruned stream through the kept-index list
+                d.n_store = (int)rows.size();
+                d.map_off = put_map(A, rows, d.n_pad);
+            }
+            (void)H;
+        };
+        {
+            const std::vector<int> r0 = kept_rows(L[0]);
+            pack_layer(A, L[0], r0, identity_map(N.C_in), D.cin_pad0, D.layers[0]);
+            io(D.layers[0], BUF_XQ, 0, D.cin_pad0, BUF_A, 0, rw, MODE_ACT);
+            stream_out(L[0], D.layers[0], r0);
+            D.zero_a = (int)r0.size() != Wd;
+        }
+        for (int l = 1; l + 1 < nl; l += 2) {
+            const std::vector<int> r1 = kept_rows(L[l]);
+            const int tw = round64((int)r1.size());
+            buf_w[BUF_B] = std::max(buf_w[BUF_B], tw);
+            pack_layer(A, L[l], r1, identity_map(Wd), rw, D.layers[l]);
+            io(D.layers[l], BUF_A, 0, rw, BUF_B, 0, tw, MODE_ACT);
+            D.layers[l].n_store = tw;
+            const std::vector<int> r2 = kept_rows(L[l + 1]);
+            pack_layer(A, L[l + 1], r2, rank_map(L[l], 0), tw, D.layers[l + 1]);
+            io(D.layers[l + 1], BUF_B, 0, tw, BUF_A, 0, rw, MODE_ACT);
+            stream_out(L[l + 1], D.layers[l + 1], r2);
+        }
+        pack_layer(A, L[nl - 1], kept_rows(L[nl - 1]), identity_map(Wd), rw, D.layers[nl - 1]);
+        io(D.layers[nl - 1], BUF_A, 0, rw, -1, 0, 0, last_mode);
+        D.layers[nl - 1].n_store = N.C_out;
+    } else {
+        // BUF_A: concatenation of the compacted feature blocks f0..f_depth; BUF_B: bottleneck g
+        const int depth = (nl - 2) / 2;
+        const int Wd = L[0].C_out;
+        std::vector<int> blk_off(depth + 2, 0);
+        std::vector<int> catpos;  // packed column of every original concat channel
+        for (int j = 0; j <= depth; ++j) {
+            const HostLayer& P = j == 0 ? L[0] : L[2 * j];
+            const std::vector<int> pm = rank_map(P, blk_off[j]);
+            catpos.insert(catpos.end(), pm.begin(), pm.end());
+            blk_off[j + 1] = blk_off[j] + round64((int)kept_rows(P).size());
+        }
+        const int cw = blk_off[depth + 1];
+        D.a_stride = cw;
+        buf_w[BUF_A] = std::max(buf_w[BUF_A], cw);
+        pack_layer(A, L[0], kept_rows(L[0]), identity_map(N.C_in), D.cin_pad0, D.layers[0]);
+        io(D.layers[0], BUF_XQ, 0, D.cin_pad0, BUF_A, 0, cw, MODE_ACT);
+        D.layers[0].n_store = blk_off[1];
+        for (int l = 1; l <= depth; ++l) {
+            const HostLayer &P1 = L[2 * l - 1], &P3 = L[2 * l];
+            const int gw = round64((int)kept_rows(P1).size());
+            buf_w[BUF_B] = std::max(buf_w[BUF_B], gw);
+            std::vector<int> cols(catpos.begin(), catpos.begin() + (size_t)l * Wd);
+            pack_layer(A, P1, kept_rows(P1), cols, blk_off[l], D.layers[2 * l - 1]);
+            io(D.layers[2 * l - 1], BUF_A, 0, cw, BUF_B, 0, gw, MODE_ACT);
+            D.layers[2 * l - 1].n_store = gw;
+            pack_layer(A, P3, kept_rows(P3), rank_map(P1, 0), gw, D.layers[2 * l]);
+            io(D.layers[2 * l], BUF_B, 0, gw, BUF_A, blk_off[l], cw, MODE_ACT);
+            D.layers[2 * l].n_store = blk_off[l + 1] - blk_off[l];
+        }
+        pack_layer(A, L[nl - 1], kept_rows(L[nl - 1]), catpos, cw, D.layers[nl - 1]);
+        io(D.layers[nl - 1], BUF_A, 0, cw, -1, 0, 0, last_mode);
+        D.layers[nl - 1].n_store = N.C_out;
+    }
+}
+
+}  // namespace
+
+struct iodf_ctx {
+    int device = 0, max_batch = 0;
+    HostModel shape;  // header fields only are used after init
+    std::vector<DevNet> nets;
+    std::vector<int> first_net;       // per level (1-based)
+    std::vector<long long> z_off;     // per level
+    std::vector<long long> code_off;  // per level with a head
+    long long d = 0, d_codes = 0;
+    uint8_t* params = nullptr;        // packed weights, constants, index maps
+    size_t params_bytes = 0;
+    int8_t* buf[NUM_BUFS] = {nullptr, nullptr, nullptr};
+    int buf_w[NUM_BUFS] = {0, 0, 0};
+    std::vector<int32_t*> state;      // per level (1-based), int32 [B][h][w][C]
+    unsigned long long* range_errs = nullptr;
+    size_t workspace_bytes = 0;
+    long long macs_fwd = 0, macs_inv = 0, macs_wide = 0;
+    int conv_launches = 0;
+    // optional per-launch timing (iodf_profile_begin / iodf_profile_end)
+    struct ProfRec { int cls; long long macs, bytes; };
+    bool prof_on = false;
+    std::vector<hipEvent_t> prof_ev;
+    std::vector<ProfRec> prof_recs;
+};
+
+namespace {
+
+enum { CLS_QUANT_IN = 0, CLS_FILL_ZERO, CLS_INGEST, CLS_FACTOR_OUT, CLS_UNFACTOR, CLS_EMIT_X, NUM_FLOW_CLS };
+const char* const kFlowClsName[NUM_FLOW_CLS] = {"k_quant_in", "k_fill_zero", "k_ingest_squeeze",
+                                                "k_factor_out", "k_unfactor", "k_emit_x"};
+
+bool prof_start(iodf_ctx* ctx, hipStream_t st) {
+    if (!ctx->prof_on || 2 * (ctx->prof_recs.size() + 1) > ctx->prof_ev.size()) return false;
+    return hipEventRecord(ctx->prof_ev[2 * ctx->prof_recs.size()], st) == hipSuccess;
+}
+
+void prof_stop(iodf_ctx* ctx, hipStream_t st, int cls, long long macs, long long bytes) {
+    (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_recs.size() + 1], st);
+    ctx->prof_recs.push_back({cls, macs, bytes});
+}
+
+// Launch through `call`, bracketed by events when profiling is on.
+#define PROF_LAUNCH(ctx, st, cls, macs, bytes, call)        \
+    do {                                                    \
+        const bool p__ = prof_start(ctx, st);               \
+        HIP_TRY(call);                                      \
+        if (p__) prof_stop(ctx, st, cls, macs, bytes);      \
+    } while (0)
+
+int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* codes, hipStream_t st) {
+    const int lv = N.level;
+    const int h = ctx->shape.H >> lv, w = ctx->shape.W >> lv;
+    const int npix = batch * h * w;
+    const int32_t* phi = (const int32_t*)(ctx->params + N.phi_off);
+    const int ntile = conv_num_tiles();
+    PROF_LAUNCH(ctx, st, ntile + CLS_QUANT_IN, 0, (long long)npix * (4 * N.C_in + N.cin_pad0),
+                launch_quant_in(ctx->state[lv], npix, N.C, phi, N.C_in, N.M_in, N.s_in, ctx->buf[BUF_XQ], N.cin_pad0, st));
+    if (N.zero_a)
+        PROF_LAUNCH(ctx, st, ntile + CLS_FILL_ZERO, 0, (long long)npix * N.a_stride,
+                    launch_fill_zero(ctx->buf[BUF_A], (size_t)npix * N.a_stride, st));
+    for (const DevLayer& L : N.layers) {
+        ConvArgs a;
+        memset(&a, 0, sizeof(a));
+        a.in = ctx->buf[L.in_buf];
+        a.in_stride = L.in_stride;
+        a.in_off = L.in_off;
+        a.cin_pad = L.cin_pad;
+        a.taps = L.taps;
+        a.h = h; a.w = w; a.npix = npix;
+        a.wgt = (const int8_t*)(ctx->params + L.wgt_off);
+        a.n_pad = L.n_pad;
+        a.bias = (const int32_t*)(ctx->params + L.bias_off);
+        a.mul = (const int32_t*)(ctx->params + L.mul_off);
+        a.shift = (const int32_t*)(ctx->params + L.shift_off);
+        a.n_store = L.n_store;
+        a.mode = L.mode;
+        a.relu = L.relu;
+        if (L.mode == MODE_ACT) {
+            a.out = ctx->buf[L.out_buf];
+            a.out_stride = L.out_stride;
+            a.out_off = L.out_off;
+            a.out_map = L.map_off == (size_t)-1 ? nullptr : (const int32_t*)(ctx->params + L.map_off);
+            a.shortcut = L.shortcut;
+        } else if (L.mode == MODE_COUPLE) {
+            a.state = ctx->state[lv];
+            a.state_c = N.C;
+            a.idx_b = phi + N.C_in;
+            a.sign = mode_sign;
+        } else {
+            a.codes = codes;
+            a.codes_img_stride = ctx->d_codes;
+            a.codes_off = ctx->code_off[lv];
+        }
+        const long long extra = L.mode == MODE_COUPLE ? 8LL * N.C_out : 0;  // state read + write
+        PROF_LAUNCH(ctx, st, conv_pick_tile(a), L.macs_per_pixel * npix,
+                    (L.bytes_per_pixel + extra) * npix + L.wgt_bytes, launch_conv(a, st));
+    }
+    return IODF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int iodf_last_hip_error(void) { return g_last_hip; }
+
+const char* iodf_strerror(int code) {
+    switch (code) {
+        case IODF_OK: return "ok";
+        case IODF_E_ARG: return "invalid argument";
+        case IODF_E_BLOB: return "malformed model blob";
+        case IODF_E_SHAPE: return "model layers do not fit the declared flow structure";
+        case IODF_E_BATCH: return "batch outside [0, max_batch]";
+        case IODF_E_HIP: return "HIP runtime error";
+        case IODF_E_NOMEM: return "out of memory";
+        default: return "unknown error";
+    }
+}
+
+int iodf_init(iodf_ctx** out, const void* model_blob, size_t blob_bytes, int device_ordinal, int max_batch) {
+    if (!out || !model_blob || max_batch < 1 || device_ordinal < 0) return IODF_E_ARG;
+    *out = nullptr;
+    // host-side validation comes first: it needs no GPU
+    std::vector<uint32_t> copy((blob_bytes + 3) / 4);
+    memcpy(copy.data(), model_blob, blob_bytes);
+    HostModel hm;
+    int rc = parse_blob((const uint8_t*)copy.data(), blob_bytes, hm);
+    if (rc != IODF_OK) return rc;
+    rc = check_shapes(hm);
+    if (rc != IODF_OK) return rc;
+    const long long px1 = (long long)max_batch * (hm.H / 2) * (hm.W / 2);
+    if (px1 > (1LL << 30)) return IODF_E_BATCH;
+
+    iodf_ctx* ctx = new (std::nothrow) iodf_ctx();
+    if (!ctx) return IODF_E_NOMEM;
+    ctx->device = device_ordinal;
+    ctx->max_batch = max_batch;
+    ctx->shape = hm;
+    ctx->d = 3LL * hm.H * hm.W;
+
+    // offsets of z chunks / code chunks and network indices per level
+    ctx->first_net.assign(hm.levels + 2, 0);
+    ctx->z_off.assign(hm.levels + 2, 0);
+    ctx->code_off.assign(hm.levels + 2, 0);
+    {
+        int net = 0;
+        long long zo = 0, co = 0;
+        for (int lv = 1; lv <= hm.levels; ++lv) {
+            const int C = level_channels(lv);
+            const long long hw = (long long)(hm.H >> lv) * (hm.W >> lv);
+            ctx->first_net[lv] = net;
+            ctx->z_off[lv] = zo;
+            ctx->code_off[lv] = co;
+            net += hm.couplings;
+            if (lv < hm.levels) {
+                zo += (C - C / 2) * hw;
+                if (hm.has_heads) { co += 2LL * (C - C / 2) * hw; ++net; }
+            } else {
+                zo += C * hw;
+            }
+        }
+        ctx->d_codes = co;
+    }
+
+    // plan: pack weights (gate compaction), constants and composed permutations
+    Arena A;
+    A.host.reserve(blob_bytes + blob_bytes / 2 + (1 << 20));
+    ctx->nets.resize(hm.nets.size());
+    {
+        size_t n = 0;
+        for (int lv = 1; lv <= hm.levels; ++lv) {
+            const int C = level_channels(lv);
+            std::vector<int> phi = identity_map(C);
+            size_t last_off = 0;
+            for (int k = 0; k < hm.couplings; ++k, ++n) {
+                // logical channel i after this coupling's permutation is the previous logical perm[i]
+                std::vector<int> nphi(C);
+                for (int i = 0; i < C; ++i) nphi[i] = phi[hm.nets[n].perm[i]];
+                phi.swap(nphi);
+                last_off = A.alloc(4 * (size_t)C);
+                memcpy(A.host.data() + last_off, phi.data(), 4 * (size_t)C);
+                ctx->nets[n].phi_off = last_off;
+                plan_net(A, hm, hm.nets[n], ctx->nets[n], ctx->buf_w);
+            }
+            if (hm.has_heads && lv < hm.levels) {
+                ctx->nets[n].phi_off = last_off;
+                plan_net(A, hm, hm.nets[n], ctx->nets[n], ctx->buf_w);
+                ++n;
+            }
+        }
+    }
+    ctx->shape.nets.clear();  // their pointers die with the blob copy; only header fields are kept
+    for (const DevNet& N : ctx->nets) {
+        const long long hw = (long long)(hm.H >> N.level) * (hm.W >> N.level);
+        for (const DevLayer& L : N.layers) {
+            ctx->macs_fwd += L.macs_per_pixel * hw;
+            if (N.kind == 0) ctx->macs_inv += L.macs_per_pixel * hw;
+            if (L.wide) ctx->macs_wide += L.macs_per_pixel * hw;
+            ++ctx->conv_launches;
+        }
+    }
+
+    // device side
+    hipError_t e = hipSetDevice(device_ordinal);
+    if (e == hipSuccess) e = conv_setup();
+    if (e != hipSuccess) { g_last_hip = (int)e; delete ctx; return IODF_E_HIP; }
+    auto dev_alloc = [&](void** p, size_t bytes) -> bool {
+        if (bytes == 0) bytes = 256;
+        hipError_t er = hipMalloc(p, bytes);
+        if (er != hipSuccess) { g_last_hip = (int)er; *p = nullptr; return false; }
+        ctx->workspace_bytes += bytes;
+        return true;
+    };
+    bool ok = true;
+    ctx->params_bytes = A.host.size();
+    ok = ok && dev_alloc((void**)&ctx->params, ctx->params_bytes);
+    if (ok && ctx->params_bytes) {
+        e = hipMemcpy(ctx->params, A.host.data(), ctx->params_bytes, hipMemcpyHostToDevice);
+        if (e != hipSuccess) { g_last_hip = (int)e; ok = false; }
+    }
+    for (int b = 0; b < NUM_BUFS && ok; ++b) {
+        const size_t bytes = (size_t)px1 * (size_t)std::max(ctx->buf_w[b], 64);
+        ok = dev_alloc((void**)&ctx->buf[b], bytes);
+        if (ok) { e = hipMemset(ctx->buf[b], 0, bytes); if (e != hipSuccess) { g_last_hip = (int)e; ok = false; } }
+    }
+    ctx->state.assign(hm.levels + 2, nullptr);
+    for (int lv = 1; lv <= hm.levels && ok; ++lv) {
+        const size_t bytes = 4 * (size_t)max_batch * (hm.H >> lv) * (hm.W >> lv) * level_channels(lv);
+        ok = dev_alloc((void**)&ctx->state[lv], bytes);
+    }
+    ok = ok && dev_alloc((void**)&ctx->range_errs, sizeof(unsigned long long));
+    if (ok) {
+        e = hipMemset(ctx->range_errs, 0, sizeof(unsigned long long));
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (e != hipSuccess) { g_last_hip = (int)e; ok = false; }
+    }
+    if (!ok) {
+        const bool hip_failed = g_last_hip != (int)hipErrorOutOfMemory;
+        iodf_free(ctx);
+        return hip_failed ? IODF_E_HIP : IODF_E_NOMEM;
+    }
+    *out = ctx;
+    return IODF_OK;
+}
+
+void iodf_free(iodf_ctx* ctx) {
+    if (!ctx) return;
+    (void)hipSetDevice(ctx->device);
+    if (ctx->params) (void)hipFree(ctx->params);
+    for (int b = 0; b < NUM_BUFS; ++b)
+        if (ctx->buf[b]) (void)hipFree(ctx->buf[b]);
+    for (int32_t* s : ctx->state)
+        if (s) (void)hipFree(s);
+    if (ctx->range_errs) (void)hipFree(ctx->range_errs);
+    for (hipEvent_t& e : ctx->prof_ev)
+        if (e) (void)hipEventDestroy(e);
+    delete ctx;
+}
+
+int iodf_forward(iodf_ctx* ctx, const uint8_t* x_dev, int batch, int32_t* z_dev, int8_t* codes_dev, void* stream) {
+    if (!ctx) return IODF_E_ARG;
+    if (batch < 0 || batch > ctx->max_batch) return IODF_E_BATCH;
+    if (batch == 0) return IODF_OK;
+    if (!x_dev || !z_dev) return IODF_E_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipSetDevice(ctx->device));
+    const HostModel& m = ctx->shape;
+    const int ntile = conv_num_tiles();
+    PROF_LAUNCH(ctx, st, ntile + CLS_INGEST, 0, 5LL * batch * ctx->d,
+                launch_ingest_squeeze(x_dev, batch, m.H, m.W, ctx->state[1], st));
+    for (int lv = 1; lv <= m.levels; ++lv) {
+        const int C = level_channels(lv), h = m.H >> lv, w = m.W >> lv;
+        const int n0 = ctx->first_net[lv];
+        for (int k = 0; k < m.couplings; ++k) {
+            const int rc = run_net(ctx, ctx->nets[n0 + k], batch, +1, nullptr, st);
+            if (rc != IODF_OK) return rc;
+        }
+        const int32_t* phi = (const int32_t*)(ctx->params + ctx->nets[n0 + m.couplings - 1].phi_off);
+        const bool last = lv == m.levels;
+        PROF_LAUNCH(ctx, st, ntile + CLS_FACTOR_OUT, 0, 8LL * batch * C * h * w,
+                    launch_factor_out(ctx->state[lv], batch, h, w, C, phi, last ? 0 : C / 2, z_dev, ctx->d,
+                                      ctx->z_off[lv], last ? nullptr : ctx->state[lv + 1], st));
+        if (!last && m.has_heads && codes_dev) {
+            const int rc = run_net(ctx, ctx->nets[n0 + m.couplings], batch, +1, codes_dev, st);
+            if (rc != IODF_OK) return rc;
+        }
+    }
+    return IODF_OK;
+}
+
+int iodf_inverse(iodf_ctx* ctx, const int32_t* z_dev, int batch, uint8_t* x_dev, void* stream) {
+    if (!ctx) return IODF_E_ARG;
+    if (batch < 0 || batch > ctx->max_batch) return IODF_E_BATCH;
+    if (batch == 0) return IODF_OK;
+    if (!x_dev || !z_dev) return IODF_E_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipSetDevice(ctx->device));
+    const HostModel& m = ctx->shape;
+    for (int lv = m.levels; lv >= 1; --lv) {
+        const int C = level_channels(lv), h = m.H >> lv, w = m.W >> lv;
+        const int n0 = ctx->first_net[lv];
+        const int32_t* phi = (const int32_t*)(ctx->params + ctx->nets[n0 + m.couplings - 1].phi_off);
+        const bool last = lv == m.levels;
+        PROF_LAUNCH(ctx, st, conv_num_tiles() + CLS_UNFACTOR, 0, 8LL * batch * C * h * w,
+                    launch_unfactor(ctx->state[lv], batch, h, w, C, phi, last ? 0 : C / 2, z_dev, ctx->d,
+                                    ctx->z_off[lv], last ? nullptr : ctx->state[lv + 1], st));
+        for (int k = m.couplings - 1; k >= 0; --k) {
+            const int rc = run_net(ctx, ctx->nets[n0 + k], batch, -1, nullptr, st);
+            if (rc != IODF_OK) return rc;
+        }
+    }
+    PROF_LAUNCH(ctx, st, conv_num_tiles() + CLS_EMIT_X, 0, 5LL * batch * ctx->d,
+                launch_emit_x(ctx->state[1], batch, m.H, m.W, x_dev, ctx->range_errs, st));
+    return IODF_OK;
+}
+
+int iodf_profile_begin(iodf_ctx* ctx, int max_launches) {
+    if (!ctx || max_launches < 1 || max_launches > (1 << 22)) return IODF_E_ARG;
+    if (ctx->prof_on) return IODF_E_ARG;
+    HIP_TRY(hipSetDevice(ctx->device));
+    ctx->prof_ev.assign(2 * (size_t)max_launches, nullptr);
+    for (hipEvent_t& e : ctx->prof_ev) {
+        const hipError_t er = hipEventCreate(&e);
+        if (er != hipSuccess) {
+            for (hipEvent_t& d : ctx->prof_ev)
+                if (d) (void)hipEventDestroy(d);
+            ctx->prof_ev.clear();
+            g_last_hip = (int)er;
+            return IODF_E_HIP;
+        }
+    }
+    ctx->prof_recs.clear();
+    ctx->prof_recs.reserve((size_t)max_launches);
+    ctx->prof_on = true;
+    return IODF_OK;
+}
+
+int iodf_profile_end(iodf_ctx* ctx, iodf_kernel_stat* stats, int max_stats, int* n_stats) {
+    if (!ctx || !stats || !n_stats || max_stats < 1) return IODF_E_ARG;
+    if (!ctx->prof_on) return IODF_E_ARG;
+    ctx->prof_on = false;
+    const int ntile = conv_num_tiles();
+    const int ncls = ntile + NUM_FLOW_CLS;
+    std::vector<iodf_kernel_stat> acc((size_t)ncls);
+    for (int c = 0; c < ncls; ++c) {
+        memset(&acc[c], 0, sizeof(iodf_kernel_stat));
+        const char* nm = c < ntile ? conv_tile_name(c) : kFlowClsName[c - ntile];
+        strncpy(acc[c].name, nm, sizeof(acc[c].name) - 1);
+    }
+    int rc = IODF_OK;
+    for (size_t i = 0; i < ctx->prof_recs.size(); ++i) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(ctx->prof_ev[2 * i + 1]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]);
+        if (e != hipSuccess) { g_last_hip = (int)e; rc = IODF_E_HIP; break; }
+        const iodf_ctx::ProfRec& r = ctx->prof_recs[i];
+        if (r.cls < 0 || r.cls >= ncls) continue;
+        acc[r.cls].launches += 1;
+        acc[r.cls].total_ms += ms;
+        acc[r.cls].macs += r.macs;
+        acc[r.cls].bytes += r.bytes;
+    }
+    for (hipEvent_t& e : ctx->prof_ev)
+        if (e) (void)hipEventDestroy(e);
+    ctx->prof_ev.clear();
+    ctx->prof_recs.clear();
+    int n = 0;
+    for (int c = 0; c < ncls && n < max_stats; ++c)
+        if (acc[c].launches) stats[n++] = acc[c];
+    *n_stats = n;
+    return rc;
+}
+
+int iodf_query(iodf_ctx* ctx, int what, int64_t* out) {
+    if (!ctx || !out) return IODF_E_ARG;
+    switch (what) {
+        case IODF_Q_Z_ELEMS: *out = ctx->d; return IODF_OK;
+        case IODF_Q_CODE_BYTES: *out = ctx->d_codes; return IODF_OK;
+        case IODF_Q_WORKSPACE_BYTES: *out = (int64_t)ctx->workspace_bytes; return IODF_OK;
+        case IODF_Q_MACS_FORWARD: *out = ctx->macs_fwd; return IODF_OK;
+        case IODF_Q_MACS_INVERSE: *out = ctx->macs_inv; return IODF_OK;
+        case IODF_Q_WIDE_MACS_FORWARD: *out = ctx->macs_wide; return IODF_OK;
+        case IODF_Q_MAX_BATCH: *out = ctx->max_batch; return IODF_OK;
+        case IODF_Q_IMAGE_H: *out = ctx->shape.H; return IODF_OK;
+        case IODF_Q_IMAGE_W: *out = ctx->shape.W; return IODF_OK;
+        case IODF_Q_CONV_LAUNCHES: *out = ctx->conv_launches; return IODF_OK;
+        case IODF_Q_RANGE_ERRORS: {
+            HIP_TRY(hipSetDevice(ctx->device));
+            HIP_TRY(hipDeviceSynchronize());
+            unsigned long long v = 0;
+            HIP_TRY(hipMemcpy(&v, ctx->range_errs, sizeof(v), hipMemcpyDeviceToHost));
+            HIP_TRY(hipMemset(ctx->range_errs, 0, sizeof(v)));
+            *out = (int64_t)v;
+            return IODF_OK;
+        }
+        default: return IODF_E_ARG;
+    }
+}
+
+}  // extern "C"

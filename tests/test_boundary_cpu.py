@@ -1,0 +1,86 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol
+that include/iodf.h declares, and rejects malformed models on the host before any
+GPU call is made."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2206_08869_amd as iodf
+from synth import CONFIGS, make_blob, parse_blob
+from synth.model import pack_blob
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "iodf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(iodf_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = iodf.load_library()
+    names = _declared()
+    assert set(names) == set(iodf.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_strerror_covers_codes():
+    lib = iodf.load_library()
+    seen = {lib.iodf_strerror(c).decode() for c in range(0, -7, -1)}
+    assert len(seen) == 7 and "unknown error" not in seen
+    assert lib.iodf_strerror(-99).decode() == "unknown error"
+
+
+def _init_code(blob, max_batch=1):
+    lib = iodf.load_library()
+    h = ctypes.c_void_p()
+    blob = np.ascontiguousarray(blob, dtype=np.uint8)
+    rc = lib.iodf_init(ctypes.byref(h), blob.ctypes.data_as(ctypes.c_void_p), blob.size, 0, max_batch)
+    if rc == 0:
+        lib.iodf_free(h)
+    return rc
+
+
+def test_init_rejects_bad_arguments_and_blobs_on_the_host():
+    lib = iodf.load_library()
+    good = make_blob(CONFIGS["cfg1"])
+    assert lib.iodf_init(None, None, 0, 0, 1) == -1
+    assert _init_code(good, max_batch=0) == -1
+    bad = good.copy(); bad[4] ^= 0xFF
+    assert _init_code(bad) == -2                                   # magic
+    assert _init_code(good[:-8]) == -2                             # truncated
+    assert _init_code(np.concatenate([good, np.zeros(4, np.uint8)])) == -2   # trailing bytes
+
+    def edited(fn):
+        m = parse_blob(good.copy())
+        fn(m)
+        return pack_blob(m)
+
+    assert _init_code(edited(lambda m: m["nets"][0]["layers"][0]["shift"].__setitem__(0, 63))) == -2
+    assert _init_code(edited(lambda m: m["nets"][0]["layers"][1]["M"].__setitem__(0, -1))) == -2
+    assert _init_code(edited(lambda m: m["nets"][0]["layers"][0]["bias"].__setitem__(0, 1 << 30))) == -2
+    assert _init_code(edited(lambda m: m["nets"][0]["perm"].__setitem__(0, int(m["nets"][0]["perm"][1])))) == -2
+    assert _init_code(edited(lambda m: m["nets"][0]["layers"][0]["gate"].__setitem__(slice(None), 0))) == -2
+    # well formed but not a valid flow: the translation channels may not be gated
+    assert _init_code(edited(lambda m: m["nets"][0]["layers"][1]["gate"].__setitem__(0, 0))) == -3
+    # wrong number of networks for the declared structure
+    assert _init_code(edited(lambda m: m["nets"].pop())) == -3
+    # wrong wiring: second conv of a plain t() must read the first conv's width
+    def narrow(m):
+        L = m["nets"][0]["layers"][1]
+        L["W"] = L["W"][:, :16]
+    assert _init_code(edited(narrow)) == -3
+
+
+def test_null_context_is_refused():
+    lib = iodf.load_library()
+    assert lib.iodf_forward(None, None, 1, None, None, None) == -1
+    assert lib.iodf_inverse(None, None, 1, None, None) == -1
+    v = ctypes.c_int64(0)
+    assert lib.iodf_query(None, 0, ctypes.byref(v)) == -1
+    lib.iodf_free(None)

@@ -1,0 +1,122 @@
+"""GPU parity: libiodf (HIP kernels, through the C ABI) against the CPU oracle,
+element by element and bit-exact: all arithmetic is integer, so there is no
+tolerance anywhere in this file."""
+import numpy as np
+import pytest
+
+from synth import CONFIGS
+from util import blob_of, gpu_flow, images, oracle_model, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_full(name, batch=None, kinds=("filtered",), modes=("random",)):
+    import torch
+    cfg = CONFIGS[name]
+    b = cfg.batch if batch is None else batch
+    for mode in modes:
+        om = oracle_model(name, mode)
+        flow = gpu_flow(name, max_batch=b, mode=mode)
+        for kind in kinds:
+            x = images(name, batch=b, kind=kind)
+            print("parity", name, "batch", b, "images", kind, "mode", mode, flush=True)
+            z_ref, c_ref = om.forward(x)
+            xg = to_gpu(x)
+            z, codes = flow.forward(xg)
+            torch.cuda.synchronize()
+            assert np.array_equal(z.cpu().numpy(), z_ref), "z differs"
+            if cfg.heads:
+                assert np.array_equal(codes.cpu().numpy(), c_ref), "codes differ"
+            x_ref, errs = om.inverse(z_ref, x.shape[1:])
+            assert errs == 0 and np.array_equal(x_ref, x)
+            x2 = flow.inverse(z)
+            torch.cuda.synchronize()
+            assert np.array_equal(x2.cpu().numpy(), x), "round trip differs"
+            assert flow.range_errors() == 0
+        flow.close()
+
+
+@pytest.mark.parametrize("name", ["cfg1", "mini_resnet", "mini_dense", "mini_dense_g", "mini_resnet_g",
+                                  "odd_dense_g"])
+def test_small_flows_match_oracle(name):
+    _check_full(name, kinds=("filtered", "uniform"))
+
+
+@pytest.mark.parametrize("name", ["cfg1", "mini_dense", "mini_resnet"])
+def test_degenerate_networks_match_oracle(name):
+    _check_full(name, modes=("zero", "bias_only"))
+
+
+def test_mid_dense_matches_oracle():
+    _check_full("mid_dense", batch=5)   # 5*256 pixels at level 1: ragged against every pixel tile
+
+
+def test_cfg2_full_batch_matches_oracle():
+    _check_full("cfg2")
+
+
+def test_cfg2_gated_scatter_add_matches_oracle():
+    _check_full("cfg2g")
+
+
+def test_extreme_images_and_arbitrary_latents():
+    import torch
+    name = "mini_dense"
+    cfg = CONFIGS[name]
+    om = oracle_model(name)
+    flow = gpu_flow(name, max_batch=4)
+    x = np.stack([np.zeros((3, cfg.H, cfg.W), np.uint8), np.full((3, cfg.H, cfg.W), 255, np.uint8)])
+    z_ref, c_ref = om.forward(x)
+    z, c = flow.forward(to_gpu(x))
+    assert np.array_equal(z.cpu().numpy(), z_ref) and np.array_equal(c.cpu().numpy(), c_ref)
+    # decode of latents that are no image: same pixels, same count of range errors
+    rng = np.random.default_rng(5)
+    zz = rng.integers(-300, 300, (3, cfg.d)).astype(np.int32)
+    x_ref, errs = om.inverse(zz, (3, cfg.H, cfg.W))
+    xg = flow.inverse(to_gpu(zz))
+    torch.cuda.synchronize()
+    assert errs > 0 and flow.range_errors() == errs
+    assert np.array_equal(xg.cpu().numpy(), x_ref)
+    assert flow.range_errors() == 0   # the query resets the counter
+    flow.close()
+
+
+def test_batch_edges_and_invariance():
+    import torch
+    import paper_2206_08869_amd as iodf
+    name = "mini_dense_g"
+    cfg = CONFIGS[name]
+    flow = gpu_flow(name, max_batch=7)
+    x = images(name, batch=7)
+    xg = to_gpu(x)
+    z7, c7 = flow.forward(xg)
+    z7, c7 = z7.clone(), c7.clone()
+    # image i alone == image i inside the batch; two runs are identical
+    for i in (0, 3, 6):
+        zi, ci = flow.forward(xg[i:i + 1].contiguous())
+        assert torch.equal(zi[0], z7[i]) and torch.equal(ci[0], c7[i])
+    z7b, c7b = flow.forward(xg)
+    assert torch.equal(z7, z7b) and torch.equal(c7, c7b)
+    # codes are optional
+    z_nc, none = flow.forward(xg, want_codes=False)
+    assert none is None and torch.equal(z_nc, z7)
+    # batch 0 is a no-op, batch > max_batch is refused
+    z0, c0 = flow.forward(xg[:0].contiguous())
+    assert z0.shape[0] == 0
+    with pytest.raises(iodf.IodfError) as ei:
+        flow.forward(to_gpu(images(name, batch=8)))
+    assert ei.value.code == -4
+    assert flow.query(iodf.IODF_Q_MAX_BATCH) == 7
+    flow.close()
+
+
+def test_query_reports_algorithmic_macs():
+    import paper_2206_08869_amd as iodf
+    from synth import macs_per_image
+    for name in ("cfg1", "mini_dense", "mini_dense_g", "odd_dense_g", "cfg2"):
+        cfg = CONFIGS[name]
+        flow = gpu_flow(name, max_batch=1)
+        assert flow.query(iodf.IODF_Q_MACS_FORWARD) == macs_per_image(cfg)
+        assert flow.query(iodf.IODF_Q_MACS_INVERSE) == macs_per_image(cfg, with_heads=False)
+        assert flow.query(iodf.IODF_Q_Z_ELEMS) == cfg.d and flow.query(iodf.IODF_Q_CODE_BYTES) == cfg.d_codes
+        flow.close()
