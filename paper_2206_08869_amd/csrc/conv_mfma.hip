@@ -18,10 +18,26 @@
 
 #include <stdlib.h>
 
+#include <type_traits>
+
 namespace iodf {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+
+// Compile-time loop: f(std::integral_constant<int, I>) for I = 0..N-1. Keeps every
+// accumulator index a constant so the accumulators stay in registers.
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for_impl(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for_impl<I + 1, N>(f);
+    }
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl<0, N>(f);
+}
 
 constexpr int KT = 64;    // bytes (= int8 values) of K per staged tile
 constexpr int ROWB = 80;  // LDS row stride in bytes
@@ -104,21 +120,21 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
     // accumulators start at the 32-bit bias
     v16i acc[TC][TP];
     const int half = lane >> 5, l32 = lane & 31;
-#pragma unroll
-    for (int tc = 0; tc < TC; ++tc) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
+    static_for<TC>([&](auto tc_) {
+        constexpr int tc = decltype(tc_)::value;
+        static_for<4>([&](auto g_) {
+            constexpr int g = decltype(g_)::value;
             const int nb = c0 + wc * WTC + tc * 32 + g * 8 + half * 4;
             const v4i b4 = *(const v4i*)(a.bias + nb);
-#pragma unroll
-            for (int tp = 0; tp < TP; ++tp) {
+            static_for<TP>([&](auto tp_) {
+                constexpr int tp = decltype(tp_)::value;
                 acc[tc][tp][g * 4 + 0] = b4[0];
                 acc[tc][tp][g * 4 + 1] = b4[1];
                 acc[tc][tp][g * 4 + 2] = b4[2];
                 acc[tc][tp][g * 4 + 3] = b4[3];
-            }
-        }
-    }
+            });
+        });
+    });
 
     v4i rw[WU], ra[AU];
     auto gload = [&](int tap, int cc) {
@@ -160,11 +176,13 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
             for (int tc = 0; tc < TC; ++tc) wf[tc] = *(const v4i*)(wl + tc * 32 * ROWB + ks * 32);
 #pragma unroll
             for (int tp = 0; tp < TP; ++tp) af[tp] = *(const v4i*)(al + tp * 32 * ROWB + ks * 32);
-#pragma unroll
-            for (int tc = 0; tc < TC; ++tc)
-#pragma unroll
-                for (int tp = 0; tp < TP; ++tp)
+            static_for<TC>([&](auto tc_) {
+                constexpr int tc = decltype(tc_)::value;
+                static_for<TP>([&](auto tp_) {
+                    constexpr int tp = decltype(tp_)::value;
                     acc[tc][tp] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[tc], af[tp], acc[tc][tp], 0, 0, 0);
+                });
+            });
         }
         if (more) lstore(buf ^ 1);
         __syncthreads();
@@ -172,21 +190,23 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
 
     // ---- epilogue: lane owns pixel l32 of each pixel tile and, per register quad g,
     // channels g*8 + half*4 .. +3 of each channel tile
-#pragma unroll
-    for (int tp = 0; tp < TP; ++tp) {
+    static_for<TP>([&](auto tp_) {
+        constexpr int tp = decltype(tp_)::value;
         const int m = p0 + wp * WTP + tp * 32 + l32;
-        if (m >= a.npix) continue;
-#pragma unroll
-        for (int tc = 0; tc < TC; ++tc) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
+        if (m >= a.npix) return;
+        static_for<TC>([&](auto tc_) {
+            constexpr int tc = decltype(tc_)::value;
+            static_for<4>([&](auto g_) {
+                constexpr int g = decltype(g_)::value;
                 const int nb = c0 + wc * WTC + tc * 32 + g * 8 + half * 4;
-                if (nb >= a.n_store) continue;
+                if (nb >= a.n_store) return;
                 const v4i M4 = *(const v4i*)(a.mul + nb);
                 const v4i S4 = *(const v4i*)(a.shift + nb);
                 int v[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = rq_dev(acc[tc][tp][g * 4 + e], M4[e], S4[e]);
+                v[0] = rq_dev(acc[tc][tp][g * 4 + 0], M4[0], S4[0]);
+                v[1] = rq_dev(acc[tc][tp][g * 4 + 1], M4[1], S4[1]);
+                v[2] = rq_dev(acc[tc][tp][g * 4 + 2], M4[2], S4[2]);
+                v[3] = rq_dev(acc[tc][tp][g * 4 + 3], M4[3], S4[3]);
                 if (a.mode == MODE_ACT && a.out_map == nullptr) {
                     int8_t* o = a.out + (long long)m * a.out_stride + a.out_off + nb;
                     if (a.shortcut) {
@@ -232,9 +252,9 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
                             (int8_t)sat8_dev(y);
                     }
                 }
-            }
-        }
-    }
+            });
+        });
+    });
 }
 
 namespace {
