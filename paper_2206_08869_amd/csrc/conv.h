@@ -21,13 +21,15 @@ struct ConvArgs {
     int taps;      // 1 (1x1) or 9 (3x3, pad 1, stride 1)
     int h, w;      // feature map size
     int npix;      // batch * h * w
+    const int8_t* zeros;  // at least 16 zero bytes, 16-byte aligned (source of padding taps)
     // weights: int8 [n_pad][taps][cin_pad], output channel major, K contiguous
     const int8_t* wgt;
     int n_pad;     // multiple of 64; rows n >= true C_out are zero
     // per output channel constants, length n_pad
     const int32_t* bias;
     const int32_t* mul;
-    const int32_t* shift;
+    const int32_t* shift;  // rq_fast: shift - 32 (every shift of the layer is >= 33); else the shift itself
+    int rq_fast;
     int n_store;   // channels written (<= n_pad); multiple of 4 in MODE_ACT without out_map
     int mode;
     int relu;

@@ -8,12 +8,9 @@
 // register quad: the 8-bit results pack into dword stores along the channel axis of
 // the pixel-major activation tensor.
 //
-// A workgroup computes BC channels x BP pixels. Per 64-byte k-tile it stages a
-// [BC][64] weight tile and a [BP][64] activation tile in LDS (row stride 80 bytes,
-// which makes the 16-byte fragment reads of 16 consecutive rows bank-conflict free),
-// double buffered: the global loads of tile k+1 are in flight while tile k feeds
-// the matrix cores. For 3x3 layers the activation tile of tap (ky,kx) is the tile of
-// the pixels shifted by (ky-1, kx-1); out-of-image taps are staged as zeros.
+// A workgroup computes BC channels x BP pixels, streaming 64-byte k-tiles of both operands
+// through a ring of LDS stages (see conv_igemm). For 3x3 layers the activation tile of tap
+// (ky,kx) is the tile of the pixels shifted by (ky-1, kx-1); out-of-image taps read zeros.
 #include "conv.h"
 
 #include <stdlib.h>
@@ -40,7 +37,6 @@ __device__ __forceinline__ void static_for(F&& f) {
 }
 
 constexpr int KT = 64;    // bytes (= int8 values) of K per staged tile
-constexpr int ROWB = 80;  // LDS row stride in bytes
 
 // Round-half-away-from-zero of acc * M / 2^s, clamped far outside the 8-bit range
 // (the caller saturates to 8 bit after adding at most one 8-bit shortcut).
@@ -55,178 +51,110 @@ __device__ __forceinline__ int rq_dev(int acc, int M, int s) {
 
 __device__ __forceinline__ int sat8_dev(int v) { return v > 127 ? 127 : (v < -128 ? -128 : v); }
 
-template <int BC, int BP, int WC, int WP>
-__global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, const int npb, const int ncb) {
-    constexpr int NT = WC * WP * 64;
-    constexpr int WTC = BC / WC, WTP = BP / WP;  // wave tile
-    constexpr int TC = WTC / 32, TP = WTP / 32;  // 32x32 MFMA tiles per wave
-    constexpr int WU = BC * 4 / NT, AU = BP * 4 / NT;  // 16-byte chunks per thread per k-tile
-    constexpr int STAGE = (BC + BP) * ROWB;
-    static_assert(WTC % 32 == 0 && WTP % 32 == 0, "wave tile must be a multiple of 32x32");
-    static_assert((BC * 4) % NT == 0 && (BP * 4) % NT == 0, "tile rows must divide over the threads");
+// Fast exact requantise for shifts >= 33: with u = |acc| * M = hi * 2^32 + lo, the rounding
+// constant 2^(s-1) is a multiple of 2^32, so floor((u + 2^(s-1)) / 2^s) =
+// (hi + 2^(s-33)) >> (s-32) and the low word never matters. sh = s - 32 (1..30).
+__device__ __forceinline__ int rq_fast_abs(unsigned ua, int M, int sh) {
+    return (int)((__umulhi(ua, (unsigned)M) + (1u << (sh - 1))) >> sh);
+}
 
-    extern __shared__ __align__(16) unsigned char lds[];
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wc = wave % WC, wp = wave / WC;
-
-    // Workgroups are dealt round-robin to the 8 XCDs. Give each XCD whole pixel
-    // blocks (all their channel blocks), so an activation tile is fetched into one L2 only.
-    const int bid = blockIdx.x;
-    const int xcd = bid & 7, slot = bid >> 3;
-    const int pb = (slot / ncb) * 8 + xcd, cb = slot % ncb;
-    if (pb >= npb) return;
-    const int p0 = pb * BP, c0 = cb * BC;
-
-    const int cpt = a.cin_pad / KT;  // k-tiles per tap
-    const int nkt = a.taps * cpt;
-    const long long wrow = (long long)nkt * KT;  // bytes per weight row
-    const int hw = a.h * a.w;
-
-    const int part = tid & 3;
-    const int8_t* wptr[WU];
-    int wlds[WU];
-#pragma unroll
-    for (int u = 0; u < WU; ++u) {
-        const int row = (tid >> 2) + u * (NT / 4);
-        wptr[u] = a.wgt + (long long)(c0 + row) * wrow + part * 16;
-        wlds[u] = row * ROWB + part * 16;
-    }
-    long long abase[AU];
-    unsigned amask[AU];
-    int alds[AU];
-#pragma unroll
-    for (int u = 0; u < AU; ++u) {
-        const int row = (tid >> 2) + u * (NT / 4);
-        const int m = p0 + row;
-        unsigned mask = 0;
-        if (m < a.npix) {
-            if (a.taps == 9) {
-                const int q = m % hw, i = q / a.w, j = q % a.w;
-#pragma unroll
-                for (int t = 0; t < 9; ++t) {
-                    const int ii = i + t / 3 - 1, jj = j + t % 3 - 1;
-                    if (ii >= 0 && ii < a.h && jj >= 0 && jj < a.w) mask |= 1u << t;
-                }
-            } else {
-                mask = 1u;
-            }
-        }
-        amask[u] = mask;
-        abase[u] = (long long)m * a.in_stride + a.in_off + part * 16;
-        alds[u] = BC * ROWB + row * ROWB + part * 16;
-    }
-
-    // accumulators start at the 32-bit bias
-    v16i acc[TC][TP];
+// Epilogue for plain 8-bit pixel-major stores (MODE_ACT, no scatter map, every shift >= 33,
+// n_store a multiple of 16). After the requantise each lane holds four dwords of 4 channels
+// (register quads g = 0..3: channels g*8 + half*4 ..); three rounds of v_permlane32_swap
+// between the two wave halves regroup them into 16 consecutive channels per lane, stored
+// with one 16-byte write.
+template <int TC, int TP>
+__device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc)[TC][TP], const int pix_base,
+                                                   const int ch_base, const int lane) {
     const int half = lane >> 5, l32 = lane & 31;
+    const bool pure_relu = a.relu && !a.shortcut;
     static_for<TC>([&](auto tc_) {
         constexpr int tc = decltype(tc_)::value;
-        static_for<4>([&](auto g_) {
-            constexpr int g = decltype(g_)::value;
-            const int nb = c0 + wc * WTC + tc * 32 + g * 8 + half * 4;
-            const v4i b4 = *(const v4i*)(a.bias + nb);
-            static_for<TP>([&](auto tp_) {
-                constexpr int tp = decltype(tp_)::value;
-                acc[tc][tp][g * 4 + 0] = b4[0];
-                acc[tc][tp][g * 4 + 1] = b4[1];
-                acc[tc][tp][g * 4 + 2] = b4[2];
-                acc[tc][tp][g * 4 + 3] = b4[3];
+        v4i Mq[4], Sq[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int nb = ch_base + tc * 32 + g * 8 + half * 4;
+            Mq[g] = *(const v4i*)(a.mul + nb);
+            Sq[g] = *(const v4i*)(a.shift + nb);
+        }
+        static_for<TP>([&](auto tp_) {
+            constexpr int tp = decltype(tp_)::value;
+            const int m = pix_base + tp * 32 + l32;
+            const bool live = m < a.npix;
+            int8_t* orow = a.out + (long long)(live ? m : 0) * a.out_stride + a.out_off + ch_base + tc * 32;
+            unsigned pk[4];
+            static_for<4>([&](auto g_) {
+                constexpr int g = decltype(g_)::value;
+                int y[4];
+                if (pure_relu) {
+                    // negative accumulators end at 0 whatever their magnitude
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int av = acc[tc][tp][g * 4 + e];
+                        const int r = rq_fast_abs((unsigned)(av < 0 ? 0 : av), Mq[g][e], Sq[g][e]);
+                        y[e] = r > 127 ? 127 : r;
+                    }
+                } else {
+                    int sc = 0;
+                    if (a.shortcut && live) sc = *(const int*)(orow + g * 8 + half * 4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int av = acc[tc][tp][g * 4 + e];
+                        const int sgn = av >> 31;
+                        int r = rq_fast_abs((unsigned)((av ^ sgn) - sgn), Mq[g][e], Sq[g][e]);
+                        r = (r ^ sgn) - sgn;
+                        r += (int)(int8_t)(sc >> (8 * e));
+                        if (a.relu) r = r < 0 ? 0 : r;
+                        y[e] = sat8_dev(r);
+                    }
+                }
+                pk[g] = ((unsigned)y[0] & 0xffu) | (((unsigned)y[1] & 0xffu) << 8) | (((unsigned)y[2] & 0xffu) << 16) |
+                        ((unsigned)y[3] << 24);
             });
+            // lower half holds channels {0-3, 8-11, 16-19, 24-27}, upper {4-7, 12-15, 20-23, 28-31}
+            auto s01 = __builtin_amdgcn_permlane32_swap(pk[0], pk[1], false, false);
+            auto s23 = __builtin_amdgcn_permlane32_swap(pk[2], pk[3], false, false);
+            // lower: {0-3, 4-7}, {16-19, 20-23}; upper: {8-11, 12-15}, {24-27, 28-31}
+            auto x = __builtin_amdgcn_permlane32_swap(s01[0], s23[0], false, false);
+            auto w = __builtin_amdgcn_permlane32_swap(s01[1], s23[1], false, false);
+            // lower: channels 0-15, upper: channels 16-31
+            if (live && ch_base + tc * 32 + half * 16 < a.n_store) {
+                v4i o4 = {(int)x[0], (int)w[0], (int)x[1], (int)w[1]};
+                *(v4i*)(orow + half * 16) = o4;
+            }
         });
     });
+}
 
-    v4i rw[WU], ra[AU];
-    auto gload = [&](int tap, int cc) {
-        const long long koff = (long long)(tap * cpt + cc) * KT;
-#pragma unroll
-        for (int u = 0; u < WU; ++u) rw[u] = *(const v4i*)(wptr[u] + koff);
-        const int dpix = a.taps == 9 ? (tap / 3 - 1) * a.w + (tap % 3 - 1) : 0;
-        const long long aoff = (long long)dpix * a.in_stride + cc * KT;
-#pragma unroll
-        for (int u = 0; u < AU; ++u) {
-            v4i v = {0, 0, 0, 0};
-            if ((amask[u] >> tap) & 1u) v = *(const v4i*)(a.in + abase[u] + aoff);
-            ra[u] = v;
-        }
-    };
-    auto lstore = [&](int buf) {
-        unsigned char* base = lds + buf * STAGE;
-#pragma unroll
-        for (int u = 0; u < WU; ++u) *(v4i*)(base + wlds[u]) = rw[u];
-#pragma unroll
-        for (int u = 0; u < AU; ++u) *(v4i*)(base + alds[u]) = ra[u];
-    };
-
-    gload(0, 0);
-    lstore(0);
-    __syncthreads();
-    int tap = 0, cc = 0;
-    for (int kt = 0; kt < nkt; ++kt) {
-        const int buf = kt & 1;
-        if (++cc == cpt) { cc = 0; ++tap; }
-        const bool more = kt + 1 < nkt;
-        if (more) gload(tap, cc);
-        const unsigned char* wl = lds + buf * STAGE + (wc * WTC + l32) * ROWB + half * 16;
-        const unsigned char* al = lds + buf * STAGE + BC * ROWB + (wp * WTP + l32) * ROWB + half * 16;
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            v4i wf[TC], af[TP];
-#pragma unroll
-            for (int tc = 0; tc < TC; ++tc) wf[tc] = *(const v4i*)(wl + tc * 32 * ROWB + ks * 32);
-#pragma unroll
-            for (int tp = 0; tp < TP; ++tp) af[tp] = *(const v4i*)(al + tp * 32 * ROWB + ks * 32);
-            static_for<TC>([&](auto tc_) {
-                constexpr int tc = decltype(tc_)::value;
-                static_for<TP>([&](auto tp_) {
-                    constexpr int tp = decltype(tp_)::value;
-                    acc[tc][tp] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[tc], af[tp], acc[tc][tp], 0, 0, 0);
-                });
-            });
-        }
-        if (more) lstore(buf ^ 1);
-        __syncthreads();
-    }
-
-    // ---- epilogue: lane owns pixel l32 of each pixel tile and, per register quad g,
-    // channels g*8 + half*4 .. +3 of each channel tile
+// General epilogue of one wave tile (any mode, any shift). Lane owns pixel l32 of each
+// 32-pixel tile and, per register quad g, channels g*8 + half*4 .. +3 of each 32-channel tile.
+template <int TC, int TP>
+__device__ __forceinline__ void conv_epilogue(const ConvArgs& a, v16i (&acc)[TC][TP], const int pix_base,
+                                              const int ch_base, const int lane, const int hw) {
+    const int half = lane >> 5, l32 = lane & 31;
     static_for<TP>([&](auto tp_) {
         constexpr int tp = decltype(tp_)::value;
-        const int m = p0 + wp * WTP + tp * 32 + l32;
+        const int m = pix_base + tp * 32 + l32;
         if (m >= a.npix) return;
         static_for<TC>([&](auto tc_) {
             constexpr int tc = decltype(tc_)::value;
             static_for<4>([&](auto g_) {
                 constexpr int g = decltype(g_)::value;
-                const int nb = c0 + wc * WTC + tc * 32 + g * 8 + half * 4;
+                const int nb = ch_base + tc * 32 + g * 8 + half * 4;
                 if (nb >= a.n_store) return;
                 const v4i M4 = *(const v4i*)(a.mul + nb);
-                const v4i S4 = *(const v4i*)(a.shift + nb);
+                const v4i S4 = *(const v4i*)(a.shift + nb) + (a.rq_fast ? 32 : 0);
                 int v[4];
                 v[0] = rq_dev(acc[tc][tp][g * 4 + 0], M4[0], S4[0]);
                 v[1] = rq_dev(acc[tc][tp][g * 4 + 1], M4[1], S4[1]);
                 v[2] = rq_dev(acc[tc][tp][g * 4 + 2], M4[2], S4[2]);
                 v[3] = rq_dev(acc[tc][tp][g * 4 + 3], M4[3], S4[3]);
-                if (a.mode == MODE_ACT && a.out_map == nullptr) {
-                    int8_t* o = a.out + (long long)m * a.out_stride + a.out_off + nb;
-                    if (a.shortcut) {
-                        const int sc = *(const int*)o;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] += (int)(int8_t)(sc >> (8 * e));
-                    }
-                    unsigned packed = 0;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        int y = v[e];
-                        if (a.relu) y = y < 0 ? 0 : y;
-                        packed |= ((unsigned)sat8_dev(y) & 0xffu) << (8 * e);
-                    }
-                    *(unsigned*)o = packed;
-                } else if (a.mode == MODE_ACT) {
+                if (a.mode == MODE_ACT) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         if (nb + e >= a.n_store) continue;
-                        int8_t* o = a.out + (long long)m * a.out_stride + a.out_off + a.out_map[nb + e];
+                        const int ch = a.out_map ? a.out_map[nb + e] : nb + e;
+                        int8_t* o = a.out + (long long)m * a.out_stride + a.out_off + ch;
                         int y = v[e];
                         if (a.shortcut) y += (int)*o;
                         if (a.relu) y = y < 0 ? 0 : y;
@@ -257,27 +185,203 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
     });
 }
 
+// Wait until at most N of this wave's global->LDS loads are outstanding and all of its LDS
+// reads have returned, then meet the other waves. Loads retire in order, so "at most N
+// outstanding" means every tile but the newest N / (loads per tile) has landed; the LDS-read
+// part guarantees that nobody still reads the stage the next loads will overwrite.
+template <int N>
+__device__ __forceinline__ void wait_tiles_then_barrier() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+// BC channels x BP pixels per workgroup, WC x WP waves, NST LDS stages of one 64-byte k-tile.
+//
+// Tiles go from global memory straight into LDS (global_load_lds_dwordx4): a wave-wide load
+// fills 1 KB of LDS with the 16-byte chunks of its 64 lanes in lane order, i.e. 16 rows x 64
+// bytes. Lane i fetches k-part (i & 3) ^ ((i >> 4) & 3) of row i >> 2, so the chunk of k-part
+// q of row r sits at position q ^ ((r >> 2) & 3) of the row: the 16-byte fragment reads of 16
+// consecutive rows then touch every LDS bank exactly once. NST - 1 tiles are in flight while
+// one is consumed; each lane issues the same number of loads per tile, so a constant
+// s_waitcnt vmcnt() tells when the oldest tile has landed, and one s_barrier per tile both
+// publishes it and frees the stage consumed before. Out-of-image taps and the tail beyond the
+// last tile read from a small zero buffer instead.
+template <int BC, int BP, int WC, int WP, int NST, bool FAST>
+__global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, const int npb, const int ncb) {
+    constexpr int NW = WC * WP;
+    constexpr int WTC = BC / WC, WTP = BP / WP;  // wave tile
+    constexpr int TC = WTC / 32, TP = WTP / 32;  // 32x32 MFMA tiles per wave
+    constexpr int WI = BC / 16 / NW, AI = BP / 16 / NW;  // wave-wide loads per wave per k-tile
+    constexpr int LPT = WI + AI;
+    constexpr int STAGE = (BC + BP) * KT;
+    static_assert(WTC % 32 == 0 && WTP % 32 == 0, "wave tile must be a multiple of 32x32");
+    static_assert(BC % (16 * NW) == 0 && BP % (16 * NW) == 0, "tile rows must divide over the waves");
+    static_assert(NST >= 4 && (NST - 2) * LPT < 64, "pipeline depth must fit the vmcnt counter");
+
+    extern __shared__ __align__(1024) unsigned char lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wc = wave % WC, wp = wave / WC;
+
+    // Workgroups are dealt round-robin to the 8 XCDs. Give each XCD whole pixel
+    // blocks (all their channel blocks), so an activation tile is fetched into one L2 only.
+    const int bid = blockIdx.x;
+    const int xcd = bid & 7, slot = bid >> 3;
+    const int pb = (slot / ncb) * 8 + xcd, cb = slot % ncb;
+    if (pb >= npb) return;
+    const int p0 = pb * BP, c0 = cb * BC;
+
+    const int cpt = a.cin_pad / KT;  // k-tiles per tap
+    const int nkt = a.taps * cpt;
+    const long long wrow = (long long)nkt * KT;  // bytes per weight row
+    const int hw = a.h * a.w;
+
+    // what this lane fetches in each wave-wide load
+    const int lrow = lane >> 2;
+    const int lpart = (lane & 3) ^ ((lane >> 4) & 3);
+    const int8_t* wsrc[WI];
+#pragma unroll
+    for (int u = 0; u < WI; ++u)
+        wsrc[u] = a.wgt + (long long)(c0 + (wave * WI + u) * 16 + lrow) * wrow + lpart * 16;
+    const int8_t* asrc[AI];
+    unsigned amask[AI];
+#pragma unroll
+    for (int u = 0; u < AI; ++u) {
+        const int m = p0 + (wave * AI + u) * 16 + lrow;
+        unsigned mask = 0;
+        if (m < a.npix) {
+            if (a.taps == 9) {
+                const int q = m % hw, i = q / a.w, j = q % a.w;
+#pragma unroll
+                for (int t = 0; t < 9; ++t) {
+                    const int ii = i + t / 3 - 1, jj = j + t % 3 - 1;
+                    if (ii >= 0 && ii < a.h && jj >= 0 && jj < a.w) mask |= 1u << t;
+                }
+            } else {
+                mask = 1u;
+            }
+        }
+        amask[u] = mask;
+        asrc[u] = a.in + (long long)m * a.in_stride + a.in_off + lpart * 16;
+    }
+
+    // accumulators start at the 32-bit bias
+    v16i acc[TC][TP];
+    const int half = lane >> 5, l32 = lane & 31;
+    static_for<TC>([&](auto tc_) {
+        constexpr int tc = decltype(tc_)::value;
+        static_for<4>([&](auto g_) {
+            constexpr int g = decltype(g_)::value;
+            const int nb = c0 + wc * WTC + tc * 32 + g * 8 + half * 4;
+            const v4i b4 = *(const v4i*)(a.bias + nb);
+            static_for<TP>([&](auto tp_) {
+                constexpr int tp = decltype(tp_)::value;
+                acc[tc][tp][g * 4 + 0] = b4[0];
+                acc[tc][tp][g * 4 + 1] = b4[1];
+                acc[tc][tp][g * 4 + 2] = b4[2];
+                acc[tc][tp][g * 4 + 3] = b4[3];
+            });
+        });
+    });
+    // the bias loads must not be counted among the tile loads below
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+    typedef const void __attribute__((address_space(1))) * gptr_t;
+    typedef void __attribute__((address_space(3))) * lptr_t;
+    int itap = 0, icc = 0, itile = 0;  // next tile to issue
+    auto issue = [&]() {
+        unsigned char* sb = lds + (itile % NST) * STAGE;
+        const bool live = itile < nkt;
+        const long long koff = (long long)(itap * cpt + icc) * KT;
+#pragma unroll
+        for (int u = 0; u < WI; ++u) {
+            const int8_t* src = live ? wsrc[u] + koff : a.zeros;
+            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(sb + (wave * WI + u) * 1024), 16, 0, 0);
+        }
+        const int dpix = a.taps == 9 ? (itap / 3 - 1) * a.w + (itap % 3 - 1) : 0;
+        const long long aoff = (long long)dpix * a.in_stride + icc * KT;
+#pragma unroll
+        for (int u = 0; u < AI; ++u) {
+            const int8_t* src = (live && ((amask[u] >> itap) & 1u)) ? asrc[u] + aoff : a.zeros;
+            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(sb + BC * KT + (wave * AI + u) * 1024), 16, 0, 0);
+        }
+        ++itile;
+        if (++icc == cpt) { icc = 0; ++itap; }
+    };
+
+#pragma unroll
+    for (int t = 0; t < NST - 1; ++t) issue();
+
+    // Fragment addresses inside a stage: row l32 of each 32-row tile, k-part (2*ks + half).
+    // The loop is software pipelined: the fragments of the next 32-deep k-step are read from
+    // LDS while the matrix cores work on the current one, and the barrier that publishes tile
+    // kt+1 sits between the two k-steps of tile kt.
+    const int sw = (l32 >> 2) & 3;
+    const int off0 = (half ^ sw) * 16;
+    const int wl0 = (wc * WTC + l32) * KT, al0 = BC * KT + (wp * WTP + l32) * KT;
+    v4i wf0[TC], af0[TP], wf1[TC], af1[TP];
+    auto read_frags = [&](int stage, int ks, v4i (&wf)[TC], v4i (&af)[TP]) {
+        const unsigned char* sb = lds + stage * STAGE;
+        const int off = off0 ^ (ks * 32);
+#pragma unroll
+        for (int tc = 0; tc < TC; ++tc) wf[tc] = *(const v4i*)(sb + wl0 + tc * 32 * KT + off);
+#pragma unroll
+        for (int tp = 0; tp < TP; ++tp) af[tp] = *(const v4i*)(sb + al0 + tp * 32 * KT + off);
+    };
+    auto mma = [&](v4i (&wf)[TC], v4i (&af)[TP]) {
+        static_for<TC>([&](auto tc_) {
+            constexpr int tc = decltype(tc_)::value;
+            static_for<TP>([&](auto tp_) {
+                constexpr int tp = decltype(tp_)::value;
+                acc[tc][tp] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[tc], af[tp], acc[tc][tp], 0, 0, 0);
+            });
+        });
+    };
+    wait_tiles_then_barrier<(NST - 2) * LPT>();  // tile 0 has landed
+    read_frags(0, 0, wf0, af0);
+    for (int kt = 0; kt < nkt; ++kt) {
+        const int st = kt % NST;
+        read_frags(st, 1, wf1, af1);
+        mma(wf0, af0);
+        // Tile kt+1 has landed for everybody, and everybody is past its reads of tile kt-1,
+        // whose stage the next issue overwrites. (Past the end the tiles are zero fill.)
+        issue();
+        wait_tiles_then_barrier<(NST - 2) * LPT>();
+        read_frags((kt + 1) % NST, 0, wf0, af0);
+        mma(wf1, af1);
+    }
+    // drain the tail loads (they target stages nobody reads any more) before the wave retires
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+    if constexpr (FAST)
+        conv_epilogue_fast<TC, TP>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane);
+    else
+        conv_epilogue<TC, TP>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw);
+}
+
 namespace {
 
 struct TileCfg {
     int bc, bp;
     size_t lds;
-    void (*kern)(const ConvArgs, int, int);
+    void (*kern_fast)(const ConvArgs, int, int);
+    void (*kern_any)(const ConvArgs, int, int);
     int threads;
     const char* name;
 };
 
-#define IODF_TILE(BC, BP, WC, WP)                                                                   \
+#define IODF_TILE(BC, BP, WC, WP, NST)                                                              \
     TileCfg {                                                                                       \
-        BC, BP, (size_t)2 * (BC + BP) * ROWB, conv_igemm<BC, BP, WC, WP>, WC * WP * 64,             \
-            "conv_igemm<" #BC "," #BP "," #WC "," #WP ">"                                           \
+        BC, BP, (size_t)NST * (BC + BP) * KT, conv_igemm<BC, BP, WC, WP, NST, true>,                \
+            conv_igemm<BC, BP, WC, WP, NST, false>, WC * WP * 64,                                   \
+            "conv_igemm<" #BC "," #BP "," #WC "," #WP "," #NST ">"                                  \
     }
 
 const TileCfg kTiles[] = {
-    IODF_TILE(256, 256, 2, 2),
-    IODF_TILE(128, 128, 2, 2),
-    IODF_TILE(64, 256, 1, 4),
-    IODF_TILE(64, 64, 2, 2),
+    IODF_TILE(256, 256, 2, 2, 4),
+    IODF_TILE(128, 128, 2, 2, 4),
+    IODF_TILE(64, 256, 1, 4, 4),
+    IODF_TILE(64, 64, 2, 2, 4),
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -293,7 +397,7 @@ bool args_ok(const ConvArgs& a) {
     return !(a.cin_pad <= 0 || a.cin_pad % KT || a.n_pad <= 0 || a.n_pad % 64 || (a.taps != 1 && a.taps != 9) ||
              a.in_stride % 16 || a.in_off % 16 || a.in_off + a.cin_pad > a.in_stride || a.n_store > a.n_pad ||
              a.n_store < 1 || a.h < 1 || a.w < 1 || a.npix % (a.h * a.w) || !a.in || !a.wgt || !a.bias || !a.mul ||
-             !a.shift ||
+             !a.shift || !a.zeros ||
              (a.mode == MODE_ACT &&
               (!a.out || (!a.out_map && (a.n_store % 4 || a.out_stride % 4 || a.out_off % 4 ||
                                          a.out_off + a.n_store > a.out_stride)))) ||
@@ -305,8 +409,11 @@ bool args_ok(const ConvArgs& a) {
 
 hipError_t conv_setup() {
     for (int i = 0; i < kNumTiles; ++i) {
-        hipError_t e = hipFuncSetAttribute((const void*)kTiles[i].kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)kTiles[i].lds);
+        hipError_t e = hipFuncSetAttribute((const void*)kTiles[i].kern_fast,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kTiles[i].lds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void*)kTiles[i].kern_any, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)kTiles[i].lds);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -338,7 +445,8 @@ hipError_t launch_conv(const ConvArgs& a, hipStream_t stream) {
     const TileCfg& t = kTiles[best];
     const int npb = (a.npix + t.bp - 1) / t.bp, ncb = a.n_pad / t.bc;
     const int grid = ((npb + 7) / 8) * 8 * ncb;
-    hipLaunchKernelGGL(t.kern, dim3(grid), dim3(t.threads), t.lds, stream, a, npb, ncb);
+    const bool fast = a.mode == MODE_ACT && !a.out_map && a.rq_fast && a.n_store % 16 == 0;
+    hipLaunchKernelGGL(fast ? t.kern_fast : t.kern_any, dim3(grid), dim3(t.threads), t.lds, stream, a, npb, ncb);
     return hipGetLastError();
 }
 

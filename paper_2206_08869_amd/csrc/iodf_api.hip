@@ -186,7 +186,7 @@ int check_shapes(const HostModel& m) {
 // ---- device plan -------------------------------------------------------------------
 
 struct DevLayer {
-    int taps, cin_pad, n_pad, n_store, relu, shortcut, mode;
+    int taps, cin_pad, n_pad, n_store, relu, shortcut, mode, rq_fast;
     int in_buf, in_off, in_stride;
     int out_buf, out_off, out_stride;
     size_t wgt_off, bias_off, mul_off, shift_off;  // byte offsets into the parameter arena
@@ -267,6 +267,14 @@ void pack_layer(Arena& A, const HostLayer& L, const std::vector<int>& rows, cons
         bias[n] = L.bias[r];
         mul[n] = L.M[r];
         sh[n] = L.shift[r];
+    }
+    // layers whose every shift is >= 33 take the short exact requantise (shift stored minus 32)
+    D.rq_fast = 1;
+    for (size_t n = 0; n < rows.size(); ++n)
+        if (sh[n] < 33) D.rq_fast = 0;
+    for (int n = 0; n < D.n_pad; ++n) {
+        if (n >= (int)rows.size()) { mul[n] = 0; sh[n] = D.rq_fast ? 33 : 0; }
+        if (D.rq_fast) sh[n] -= 32;
     }
     D.macs_per_pixel = (long long)rows.size() * live * taps;
     D.bytes_per_pixel = (long long)live + (long long)rows.size();
@@ -403,6 +411,7 @@ struct iodf_ctx {
     int buf_w[NUM_BUFS] = {0, 0, 0};
     std::vector<int32_t*> state;      // per level (1-based), int32 [B][h][w][C]
     unsigned long long* range_errs = nullptr;
+    int8_t* zeros = nullptr;          // 256 zero bytes: source of convolution padding
     size_t workspace_bytes = 0;
     long long macs_fwd = 0, macs_inv = 0, macs_wide = 0;
     int conv_launches = 0;
@@ -452,6 +461,7 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
         ConvArgs a;
         memset(&a, 0, sizeof(a));
         a.in = ctx->buf[L.in_buf];
+        a.zeros = ctx->zeros;
         a.in_stride = L.in_stride;
         a.in_off = L.in_off;
         a.cin_pad = L.cin_pad;
@@ -463,6 +473,7 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
         a.mul = (const int32_t*)(ctx->params + L.mul_off);
         a.shift = (const int32_t*)(ctx->params + L.shift_off);
         a.n_store = L.n_store;
+        a.rq_fast = L.rq_fast;
         a.mode = L.mode;
         a.relu = L.relu;
         if (L.mode == MODE_ACT) {
@@ -619,8 +630,10 @@ int iodf_init(iodf_ctx** out, const void* model_blob, size_t blob_bytes, int dev
         ok = dev_alloc((void**)&ctx->state[lv], bytes);
     }
     ok = ok && dev_alloc((void**)&ctx->range_errs, sizeof(unsigned long long));
+    ok = ok && dev_alloc((void**)&ctx->zeros, 256);
     if (ok) {
-        e = hipMemset(ctx->range_errs, 0, sizeof(unsigned long long));
+        e = hipMemset(ctx->zeros, 0, 256);
+        if (e == hipSuccess) e = hipMemset(ctx->range_errs, 0, sizeof(unsigned long long));
         if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e != hipSuccess) { g_last_hip = (int)e; ok = false; }
     }
@@ -642,6 +655,7 @@ void iodf_free(iodf_ctx* ctx) {
     for (int32_t* s : ctx->state)
         if (s) (void)hipFree(s);
     if (ctx->range_errs) (void)hipFree(ctx->range_errs);
+    if (ctx->zeros) (void)hipFree(ctx->zeros);
     for (hipEvent_t& e : ctx->prof_ev)
         if (e) (void)hipEventDestroy(e);
     delete ctx;
