@@ -13,16 +13,19 @@ enum ConvMode : int {
 };
 
 struct ConvArgs {
-    // input activations: int8, pixel-major; pixel p, channel c at in[p * in_stride + in_off + c]
+    // Activation tensors are int8 in 64-channel planes: pixel p, channel c of a tensor lives at
+    //   base[((chunk0 + c / 64) * plane) + p * 64 + c % 64],   plane = bytes between planes,
+    // so the 64-byte k-chunk of consecutive pixels is contiguous (whole cache lines per tile load)
+    // and a channel concatenation is a range of planes.
     const int8_t* in;
-    int in_stride;
-    int in_off;
+    long long in_plane;
+    int in_chunk0;
     int cin_pad;   // channels read per tap, multiple of 64 (padding columns have zero weights)
     int taps;      // 1 (1x1) or 9 (3x3, pad 1, stride 1)
     int h, w;      // feature map size
     int npix;      // batch * h * w
     const int8_t* zeros;  // at least 16 zero bytes, 16-byte aligned (source of padding taps)
-    // weights: int8 [n_pad][taps][cin_pad], output channel major, K contiguous
+    // weights: int8 [taps * cin_pad / 64][n_pad][64]: k-tile major, so a [channels][64] tile is contiguous
     const int8_t* wgt;
     int n_pad;     // multiple of 64; rows n >= true C_out are zero
     // per output channel constants, length n_pad
@@ -35,8 +38,8 @@ struct ConvArgs {
     int relu;
     // MODE_ACT
     int8_t* out;
-    int out_stride;
-    int out_off;
+    long long out_plane;
+    int out_chunk0;
     const int32_t* out_map;  // optional: output channel n is stored at channel out_map[n] (scatter-add)
     int shortcut;            // add the 8-bit code already stored at the output location
     // MODE_COUPLE

@@ -3,6 +3,8 @@
 // epilogue fused in.
 //
 // GEMM view: D[channel][pixel] = sum_k Wgt[channel][k] * Act[k][pixel], k = (tap, c).
+// Activations live in 64-channel planes ([c/64][pixel][64]) and weights k-tile major
+// ([k/64][channel][64]), so every staged tile is a run of whole cache lines.
 // Output channels are the MFMA "A" rows and pixels the "B" columns, so that after
 // v_mfma_i32_32x32x32_i8 every lane owns 4 consecutive channels of one pixel per
 // register quad: the 8-bit results pack into dword stores along the channel axis of
@@ -81,7 +83,10 @@ __device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc
             constexpr int tp = decltype(tp_)::value;
             const int m = pix_base + tp * 32 + l32;
             const bool live = m < a.npix;
-            int8_t* orow = a.out + (long long)(live ? m : 0) * a.out_stride + a.out_off + ch_base + tc * 32;
+            // channels ch_base + tc*32 .. +31 sit inside one 64-channel plane
+            const int ch0 = ch_base + tc * 32;
+            int8_t* orow = a.out + (long long)(a.out_chunk0 + (ch0 >> 6)) * a.out_plane +
+                           (long long)(live ? m : 0) * 64 + (ch0 & 63);
             unsigned pk[4];
             static_for<4>([&](auto g_) {
                 constexpr int g = decltype(g_)::value;
@@ -154,7 +159,8 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs& a, v16i (&acc)[TC]
                     for (int e = 0; e < 4; ++e) {
                         if (nb + e >= a.n_store) continue;
                         const int ch = a.out_map ? a.out_map[nb + e] : nb + e;
-                        int8_t* o = a.out + (long long)m * a.out_stride + a.out_off + ch;
+                        int8_t* o = a.out + (long long)(a.out_chunk0 + (ch >> 6)) * a.out_plane + (long long)m * 64 +
+                                    (ch & 63);
                         int y = v[e];
                         if (a.shortcut) y += (int)*o;
                         if (a.relu) y = y < 0 ? 0 : y;
@@ -233,7 +239,7 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
 
     const int cpt = a.cin_pad / KT;  // k-tiles per tap
     const int nkt = a.taps * cpt;
-    const long long wrow = (long long)nkt * KT;  // bytes per weight row
+    const long long wtile = (long long)a.n_pad * KT;  // bytes per weight k-tile
     const int hw = a.h * a.w;
 
     // what this lane fetches in each wave-wide load
@@ -242,7 +248,7 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
     const int8_t* wsrc[WI];
 #pragma unroll
     for (int u = 0; u < WI; ++u)
-        wsrc[u] = a.wgt + (long long)(c0 + (wave * WI + u) * 16 + lrow) * wrow + lpart * 16;
+        wsrc[u] = a.wgt + (long long)(c0 + (wave * WI + u) * 16 + lrow) * KT + lpart * 16;
     const int8_t* asrc[AI];
     unsigned amask[AI];
 #pragma unroll
@@ -262,7 +268,7 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
             }
         }
         amask[u] = mask;
-        asrc[u] = a.in + (long long)m * a.in_stride + a.in_off + lpart * 16;
+        asrc[u] = a.in + (long long)a.in_chunk0 * a.in_plane + (long long)m * KT + lpart * 16;
     }
 
     // accumulators start at the 32-bit bias
@@ -292,14 +298,14 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
     auto issue = [&]() {
         unsigned char* sb = lds + (itile % NST) * STAGE;
         const bool live = itile < nkt;
-        const long long koff = (long long)(itap * cpt + icc) * KT;
+        const long long koff = (long long)(itap * cpt + icc) * wtile;
 #pragma unroll
         for (int u = 0; u < WI; ++u) {
             const int8_t* src = live ? wsrc[u] + koff : a.zeros;
             __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(sb + (wave * WI + u) * 1024), 16, 0, 0);
         }
         const int dpix = a.taps == 9 ? (itap / 3 - 1) * a.w + (itap % 3 - 1) : 0;
-        const long long aoff = (long long)dpix * a.in_stride + icc * KT;
+        const long long aoff = (long long)icc * a.in_plane + (long long)dpix * KT;
 #pragma unroll
         for (int u = 0; u < AI; ++u) {
             const int8_t* src = (live && ((amask[u] >> itap) & 1u)) ? asrc[u] + aoff : a.zeros;
@@ -395,12 +401,11 @@ int forced_tile() {
 
 bool args_ok(const ConvArgs& a) {
     return !(a.cin_pad <= 0 || a.cin_pad % KT || a.n_pad <= 0 || a.n_pad % 64 || (a.taps != 1 && a.taps != 9) ||
-             a.in_stride % 16 || a.in_off % 16 || a.in_off + a.cin_pad > a.in_stride || a.n_store > a.n_pad ||
+             a.in_plane < (long long)a.npix * KT || a.in_plane % 16 || a.in_chunk0 < 0 || a.n_store > a.n_pad ||
              a.n_store < 1 || a.h < 1 || a.w < 1 || a.npix % (a.h * a.w) || !a.in || !a.wgt || !a.bias || !a.mul ||
              !a.shift || !a.zeros ||
              (a.mode == MODE_ACT &&
-              (!a.out || (!a.out_map && (a.n_store % 4 || a.out_stride % 4 || a.out_off % 4 ||
-                                         a.out_off + a.n_store > a.out_stride)))) ||
+              (!a.out || a.out_plane < (long long)a.npix * KT || a.out_plane % 16 || a.out_chunk0 < 0)) ||
              (a.mode == MODE_COUPLE && (!a.state || !a.idx_b || a.state_c < 1)) ||
              (a.mode == MODE_CODES && !a.codes) || a.mode < MODE_ACT || a.mode > MODE_CODES);
 }

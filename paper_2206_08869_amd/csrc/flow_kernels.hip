@@ -55,7 +55,8 @@ __device__ __forceinline__ int rq_in(int a, int M, int s) {
     return r > 127 ? 127 : (r < -128 ? -128 : (int)r);
 }
 
-// xq[p][c] = sat8(rq(S[p][idx[c]]; M, s)) for c < n_a, 0 for n_a <= c < cpad. One thread per 4 channels.
+// Codes of channel c < n_a of pixel p: sat8(rq(S[p][idx[c]]; M, s)); channels n_a..cpad-1 are 0.
+// xq is laid out in 64-channel planes: xq[(c / 64) * npix * 64 + p * 64 + c % 64]. One thread per 4 channels.
 __global__ void k_quant_in(const int32_t* __restrict__ S, int npix, int C, const int32_t* __restrict__ idx, int n_a,
                            int M, int s, int8_t* __restrict__ xq, int cpad) {
     const int groups = cpad / 4;
@@ -71,7 +72,8 @@ __global__ void k_quant_in(const int32_t* __restrict__ S, int npix, int C, const
             if (c < n_a) v = rq_in(S[p * C + idx[c]], M, s);
             packed |= ((unsigned)v & 0xffu) << (8 * e);
         }
-        *(unsigned*)(xq + p * cpad + g * 4) = packed;
+        const int c0 = g * 4;
+        *(unsigned*)(xq + ((long long)(c0 >> 6) * npix + p) * 64 + (c0 & 63)) = packed;
     }
 }
 
@@ -146,7 +148,7 @@ hipError_t launch_emit_x(const int32_t* s1, int B, int H, int W, uint8_t* x, uns
 hipError_t launch_quant_in(const int32_t* S, int npix, int C, const int32_t* idx, int n_a, int M, int s, int8_t* xq,
                            int cpad, hipStream_t st) {
     if (npix <= 0) return hipSuccess;
-    if (cpad % 4 || n_a > cpad) return hipErrorInvalidValue;
+    if (cpad % 64 || n_a > cpad) return hipErrorInvalidValue;
     hipLaunchKernelGGL(k_quant_in, dim3(grid_for((long long)npix * (cpad / 4))), dim3(TPB), 0, st, S, npix, C, idx, n_a,
                        M, s, xq, cpad);
     return hipGetLastError();

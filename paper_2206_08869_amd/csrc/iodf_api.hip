@@ -187,8 +187,8 @@ int check_shapes(const HostModel& m) {
 
 struct DevLayer {
     int taps, cin_pad, n_pad, n_store, relu, shortcut, mode, rq_fast;
-    int in_buf, in_off, in_stride;
-    int out_buf, out_off, out_stride;
+    int in_buf, in_off;    // input tensor: buffer and first channel (multiple of 64)
+    int out_buf, out_off;  // output tensor (MODE_ACT)
     size_t wgt_off, bias_off, mul_off, shift_off;  // byte offsets into the parameter arena
     size_t map_off;                                // (size_t)-1 when there is no scatter map
     long long macs_per_pixel;                      // algorithmic: kept rows x live columns x taps
@@ -258,11 +258,14 @@ void pack_layer(Arena& A, const HostLayer& L, const std::vector<int>& rows, cons
     for (size_t n = 0; n < rows.size(); ++n) {
         const int r = rows[n];
         const int8_t* src = L.W + (size_t)r * L.C_in * taps;
-        int8_t* dst = w + n * (size_t)taps * cin_pad;
+        // k = t * cin_pad + pc; element (n, k) goes to tile k / 64, row n, byte k % 64
         for (int c = 0; c < L.C_in; ++c) {
             const int pc = colpos[c];
             if (pc < 0) continue;
-            for (int t = 0; t < taps; ++t) dst[(size_t)t * cin_pad + pc] = src[(size_t)c * taps + t];
+            for (int t = 0; t < taps; ++t) {
+                const size_t k = (size_t)t * cin_pad + pc;
+                w[((k >> 6) * D.n_pad + n) * 64 + (k & 63)] = src[(size_t)c * taps + t];
+            }
         }
         bias[n] = L.bias[r];
         mul[n] = L.M[r];
@@ -306,9 +309,9 @@ void plan_net(Arena& A, const HostModel& m, const HostNet& N, DevNet& D, int buf
     D.layers.resize(nl);
     buf_w[BUF_XQ] = std::max(buf_w[BUF_XQ], D.cin_pad0);
     const int last_mode = N.kind == 0 ? MODE_COUPLE : MODE_CODES;
-    auto io = [](DevLayer& d, int ib, int ioff, int istr, int ob, int ooff, int ostr, int mode) {
-        d.in_buf = ib; d.in_off = ioff; d.in_stride = istr;
-        d.out_buf = ob; d.out_off = ooff; d.out_stride = ostr;
+    auto io = [](DevLayer& d, int ib, int ioff, int /*in width*/, int ob, int ooff, int /*out width*/, int mode) {
+        d.in_buf = ib; d.in_off = ioff;
+        d.out_buf = ob; d.out_off = ooff;
         d.mode = mode;
     };
     if (m.family == FAM_PLAIN) {
@@ -460,10 +463,11 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
     for (const DevLayer& L : N.layers) {
         ConvArgs a;
         memset(&a, 0, sizeof(a));
+        const long long plane = (long long)npix * 64;  // bytes between 64-channel planes in every buffer
         a.in = ctx->buf[L.in_buf];
         a.zeros = ctx->zeros;
-        a.in_stride = L.in_stride;
-        a.in_off = L.in_off;
+        a.in_plane = plane;
+        a.in_chunk0 = L.in_off / 64;
         a.cin_pad = L.cin_pad;
         a.taps = L.taps;
         a.h = h; a.w = w; a.npix = npix;
@@ -478,8 +482,8 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
         a.relu = L.relu;
         if (L.mode == MODE_ACT) {
             a.out = ctx->buf[L.out_buf];
-            a.out_stride = L.out_stride;
-            a.out_off = L.out_off;
+            a.out_plane = plane;
+            a.out_chunk0 = L.out_off / 64;
             a.out_map = L.map_off == (size_t)-1 ? nullptr : (const int32_t*)(ctx->params + L.map_off);
             a.shortcut = L.shortcut;
         } else if (L.mode == MODE_COUPLE) {
