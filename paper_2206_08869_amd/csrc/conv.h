@@ -13,10 +13,14 @@ enum ConvMode : int {
 };
 
 struct ConvArgs {
-    // Activation tensors are int8 in 64-channel planes: pixel p, channel c of a tensor lives at
-    //   base[((chunk0 + c / 64) * plane) + p * 64 + c % 64],   plane = bytes between planes,
-    // so the 64-byte k-chunk of consecutive pixels is contiguous (whole cache lines per tile load)
-    // and a channel concatenation is a range of planes.
+    // Activation tensors are int8 in 64-channel planes of zero-bordered images: pixel (b, i, j),
+    // channel c lives at
+    //   base[(chunk0 + c / 64) * plane + pos(b, i, j) * 64 + c % 64],
+    //   pos(b, i, j) = b * (h + 2) * (w + 2) + (i + 1) * (w + 2) + (j + 1),
+    // plane = bytes between planes (a fixed property of the buffer, >= batch * (h+2) * (w+2) * 64).
+    // The 64-byte k-chunks of consecutive pixels are contiguous (whole cache lines per tile load),
+    // a channel concatenation is a range of planes, and the border positions hold zeros that
+    // nobody ever overwrites: they are the convolution's zero padding.
     const int8_t* in;
     long long in_plane;
     int in_chunk0;
@@ -24,7 +28,6 @@ struct ConvArgs {
     int taps;      // 1 (1x1) or 9 (3x3, pad 1, stride 1)
     int h, w;      // feature map size
     int npix;      // batch * h * w
-    const int8_t* zeros;  // at least 16 zero bytes, 16-byte aligned (source of padding taps)
     // weights: int8 [taps * cin_pad / 64][n_pad][64]: k-tile major, so a [channels][64] tile is contiguous
     const int8_t* wgt;
     int n_pad;     // multiple of 64; rows n >= true C_out are zero

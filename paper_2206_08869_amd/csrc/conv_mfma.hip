@@ -12,7 +12,7 @@
 //
 // A workgroup computes BC channels x BP pixels, streaming 64-byte k-tiles of both operands
 // through a ring of LDS stages (see conv_igemm). For 3x3 layers the activation tile of tap
-// (ky,kx) is the tile of the pixels shifted by (ky-1, kx-1); out-of-image taps read zeros.
+// (ky,kx) is the tile of the pixels shifted by (ky-1, kx-1) inside zero-bordered images.
 #include "conv.h"
 
 #include <stdlib.h>
@@ -67,8 +67,18 @@ __device__ __forceinline__ int rq_fast_abs(unsigned ua, int M, int sh) {
 // with one 16-byte write.
 template <int TC, int TP>
 __device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc)[TC][TP], const int pix_base,
-                                                   const int ch_base, const int lane) {
+                                                   const int ch_base, const int lane, const int hw) {
     const int half = lane >> 5, l32 = lane & 31;
+    const int W2 = a.w + 2, PP = (a.h + 2) * W2;
+    // position of each of this lane's pixels in the zero-bordered plane
+    long long ppos[TP];
+#pragma unroll
+    for (int tp = 0; tp < TP; ++tp) {
+        int m = pix_base + tp * 32 + l32;
+        m = m < a.npix ? m : 0;
+        const int b = m / hw, q = m - b * hw, i = q / a.w, j = q - i * a.w;
+        ppos[tp] = (long long)(b * PP + (i + 1) * W2 + (j + 1)) * 64;
+    }
     const bool pure_relu = a.relu && !a.shortcut;
     static_for<TC>([&](auto tc_) {
         constexpr int tc = decltype(tc_)::value;
@@ -85,8 +95,7 @@ __device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc
             const bool live = m < a.npix;
             // channels ch_base + tc*32 .. +31 sit inside one 64-channel plane
             const int ch0 = ch_base + tc * 32;
-            int8_t* orow = a.out + (long long)(a.out_chunk0 + (ch0 >> 6)) * a.out_plane +
-                           (long long)(live ? m : 0) * 64 + (ch0 & 63);
+            int8_t* orow = a.out + (long long)(a.out_chunk0 + (ch0 >> 6)) * a.out_plane + ppos[tp] + (ch0 & 63);
             unsigned pk[4];
             static_for<4>([&](auto g_) {
                 constexpr int g = decltype(g_)::value;
@@ -159,8 +168,9 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs& a, v16i (&acc)[TC]
                     for (int e = 0; e < 4; ++e) {
                         if (nb + e >= a.n_store) continue;
                         const int ch = a.out_map ? a.out_map[nb + e] : nb + e;
-                        int8_t* o = a.out + (long long)(a.out_chunk0 + (ch >> 6)) * a.out_plane + (long long)m * 64 +
-                                    (ch & 63);
+                        const int bi = m / hw, qi = m - bi * hw, ii = qi / a.w, ji = qi - ii * a.w;
+                        const long long pp = (long long)bi * ((a.h + 2) * (a.w + 2)) + (ii + 1) * (a.w + 2) + (ji + 1);
+                        int8_t* o = a.out + (long long)(a.out_chunk0 + (ch >> 6)) * a.out_plane + pp * 64 + (ch & 63);
                         int y = v[e];
                         if (a.shortcut) y += (int)*o;
                         if (a.relu) y = y < 0 ? 0 : y;
@@ -210,8 +220,9 @@ __device__ __forceinline__ void wait_tiles_then_barrier() {
 // consecutive rows then touch every LDS bank exactly once. NST - 1 tiles are in flight while
 // one is consumed; each lane issues the same number of loads per tile, so a constant
 // s_waitcnt vmcnt() tells when the oldest tile has landed, and one s_barrier per tile both
-// publishes it and frees the stage consumed before. Out-of-image taps and the tail beyond the
-// last tile read from a small zero buffer instead.
+// publishes it and frees the stage consumed before. Activation planes carry a one-pixel zero
+// border per image, so a 3x3 tap is a constant address shift and needs no bounds test; all
+// per-tile address arithmetic is scalar, the per-lane parts are computed once.
 template <int BC, int BP, int WC, int WP, int NST, bool FAST>
 __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, const int npb, const int ncb) {
     constexpr int NW = WC * WP;
@@ -226,7 +237,8 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
 
     extern __shared__ __align__(1024) unsigned char lds[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
     const int wc = wave % WC, wp = wave / WC;
 
     // Workgroups are dealt round-robin to the 8 XCDs. Give each XCD whole pixel
@@ -241,35 +253,25 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
     const int nkt = a.taps * cpt;
     const long long wtile = (long long)a.n_pad * KT;  // bytes per weight k-tile
     const int hw = a.h * a.w;
+    const int W2 = a.w + 2, PP = (a.h + 2) * W2;  // zero-bordered image geometry
 
-    // what this lane fetches in each wave-wide load
+    // What this lane fetches in each wave-wide load: k-part lpart of row lrow of a 16-row
+    // segment. Weight segments are contiguous, so the lane offset is a constant; activation
+    // rows are pixels, whose position in the bordered plane is computed once here. Rows past
+    // the last pixel re-read the last pixel (their results are never stored).
     const int lrow = lane >> 2;
     const int lpart = (lane & 3) ^ ((lane >> 4) & 3);
-    const int8_t* wsrc[WI];
-#pragma unroll
-    for (int u = 0; u < WI; ++u)
-        wsrc[u] = a.wgt + (long long)(c0 + (wave * WI + u) * 16 + lrow) * KT + lpart * 16;
-    const int8_t* asrc[AI];
-    unsigned amask[AI];
+    const unsigned woffl = (unsigned)(lrow * KT + lpart * 16);
+    unsigned aoffl[AI];
 #pragma unroll
     for (int u = 0; u < AI; ++u) {
-        const int m = p0 + (wave * AI + u) * 16 + lrow;
-        unsigned mask = 0;
-        if (m < a.npix) {
-            if (a.taps == 9) {
-                const int q = m % hw, i = q / a.w, j = q % a.w;
-#pragma unroll
-                for (int t = 0; t < 9; ++t) {
-                    const int ii = i + t / 3 - 1, jj = j + t % 3 - 1;
-                    if (ii >= 0 && ii < a.h && jj >= 0 && jj < a.w) mask |= 1u << t;
-                }
-            } else {
-                mask = 1u;
-            }
-        }
-        amask[u] = mask;
-        asrc[u] = a.in + (long long)a.in_chunk0 * a.in_plane + (long long)m * KT + lpart * 16;
+        int m = p0 + (wave * AI + u) * 16 + lrow;
+        m = m < a.npix ? m : a.npix - 1;
+        const int b = m / hw, q = m - b * hw, i = q / a.w, j = q - i * a.w;
+        aoffl[u] = (unsigned)(b * PP + (i + 1) * W2 + (j + 1)) * KT + (unsigned)(lpart * 16);
     }
+    const int8_t* const wbase = a.wgt + (long long)(c0 + wave * WI * 16) * KT;
+    const int8_t* const abase = a.in + (long long)a.in_chunk0 * a.in_plane;
 
     // accumulators start at the 32-bit bias
     v16i acc[TC][TP];
@@ -294,25 +296,26 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
 
     typedef const void __attribute__((address_space(1))) * gptr_t;
     typedef void __attribute__((address_space(3))) * lptr_t;
-    int itap = 0, icc = 0, itile = 0;  // next tile to issue
+    // Next tile to issue: (itap, icc), all scalar. Past the last tile the last one is loaded
+    // again into a stage nobody reads, which keeps the number of loads per step constant.
+    int itap = 0, icc = 0, itile = 0;
     auto issue = [&]() {
         unsigned char* sb = lds + (itile % NST) * STAGE;
-        const bool live = itile < nkt;
-        const long long koff = (long long)(itap * cpt + icc) * wtile;
+        const int8_t* wt = wbase + (long long)(itap * cpt + icc) * wtile;
 #pragma unroll
-        for (int u = 0; u < WI; ++u) {
-            const int8_t* src = live ? wsrc[u] + koff : a.zeros;
-            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(sb + (wave * WI + u) * 1024), 16, 0, 0);
-        }
-        const int dpix = a.taps == 9 ? (itap / 3 - 1) * a.w + (itap % 3 - 1) : 0;
-        const long long aoff = (long long)icc * a.in_plane + (long long)dpix * KT;
+        for (int u = 0; u < WI; ++u)
+            __builtin_amdgcn_global_load_lds((gptr_t)(wt + u * 1024 + woffl), (lptr_t)(sb + (wave * WI + u) * 1024), 16,
+                                             0, 0);
+        // tap (ky, kx) reads the pixel at (i + ky - 1, j + kx - 1): a constant shift in the
+        // bordered plane, and the border supplies the zero padding
+        const int dpix = a.taps == 9 ? (itap / 3 - 1) * W2 + (itap % 3 - 1) : 0;
+        const int8_t* at = abase + (long long)icc * a.in_plane + (long long)dpix * KT;
 #pragma unroll
-        for (int u = 0; u < AI; ++u) {
-            const int8_t* src = (live && ((amask[u] >> itap) & 1u)) ? asrc[u] + aoff : a.zeros;
-            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(sb + BC * KT + (wave * AI + u) * 1024), 16, 0, 0);
-        }
+        for (int u = 0; u < AI; ++u)
+            __builtin_amdgcn_global_load_lds((gptr_t)(at + aoffl[u]), (lptr_t)(sb + BC * KT + (wave * AI + u) * 1024),
+                                             16, 0, 0);
         ++itile;
-        if (++icc == cpt) { icc = 0; ++itap; }
+        if (itile < nkt && ++icc == cpt) { icc = 0; ++itap; }
     };
 
 #pragma unroll
@@ -360,7 +363,7 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     if constexpr (FAST)
-        conv_epilogue_fast<TC, TP>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane);
+        conv_epilogue_fast<TC, TP>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw);
     else
         conv_epilogue<TC, TP>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw);
 }
@@ -384,6 +387,8 @@ struct TileCfg {
     }
 
 const TileCfg kTiles[] = {
+    IODF_TILE(256, 256, 2, 4, 4),
+    IODF_TILE(256, 256, 4, 2, 4),
     IODF_TILE(256, 256, 2, 2, 4),
     IODF_TILE(128, 128, 2, 2, 4),
     IODF_TILE(64, 256, 1, 4, 4),
@@ -401,11 +406,13 @@ int forced_tile() {
 
 bool args_ok(const ConvArgs& a) {
     return !(a.cin_pad <= 0 || a.cin_pad % KT || a.n_pad <= 0 || a.n_pad % 64 || (a.taps != 1 && a.taps != 9) ||
-             a.in_plane < (long long)a.npix * KT || a.in_plane % 16 || a.in_chunk0 < 0 || a.n_store > a.n_pad ||
+             a.in_plane < (long long)(a.npix / (a.h * a.w)) * (a.h + 2) * (a.w + 2) * KT || a.in_plane % 1024 ||
+             a.in_plane >= (1LL << 31) || a.in_chunk0 < 0 || a.n_store > a.n_pad ||
              a.n_store < 1 || a.h < 1 || a.w < 1 || a.npix % (a.h * a.w) || !a.in || !a.wgt || !a.bias || !a.mul ||
-             !a.shift || !a.zeros ||
+             !a.shift ||
              (a.mode == MODE_ACT &&
-              (!a.out || a.out_plane < (long long)a.npix * KT || a.out_plane % 16 || a.out_chunk0 < 0)) ||
+              (!a.out || a.out_plane < (long long)(a.npix / (a.h * a.w)) * (a.h + 2) * (a.w + 2) * KT ||
+               a.out_plane % 64 || a.out_chunk0 < 0)) ||
              (a.mode == MODE_COUPLE && (!a.state || !a.idx_b || a.state_c < 1)) ||
              (a.mode == MODE_CODES && !a.codes) || a.mode < MODE_ACT || a.mode > MODE_CODES);
 }
@@ -433,10 +440,10 @@ int conv_pick_tile(const ConvArgs& a) {
     int best = -1;
     long long best_blocks = -1;
     const int forced = forced_tile();
+    if (forced >= 0 && forced < kNumTiles && a.n_pad % kTiles[forced].bc == 0) return forced;
     for (int i = 0; i < kNumTiles; ++i) {
         if (a.n_pad % kTiles[i].bc) continue;
         const long long blocks = (long long)((a.npix + kTiles[i].bp - 1) / kTiles[i].bp) * (a.n_pad / kTiles[i].bc);
-        if (i == forced) return i;
         if (blocks >= 256) return i;
         if (blocks > best_blocks) { best_blocks = blocks; best = i; }
     }

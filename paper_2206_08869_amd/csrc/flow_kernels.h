@@ -11,10 +11,11 @@ namespace iodf {
 hipError_t launch_ingest_squeeze(const uint8_t* x, int B, int H, int W, int32_t* s1, hipStream_t st);
 // Inverse; pixels outside [0,255] are saturated and counted into *errs.
 hipError_t launch_emit_x(const int32_t* s1, int B, int H, int W, uint8_t* x, unsigned long long* errs, hipStream_t st);
-// 8-bit codes of the first n_a logical channels (physical idx[c]) of state S [npix][C];
-// xq holds cpad channels (multiple of 64) in 64-channel planes [cpad/64][npix][64]; channels >= n_a are 0.
-hipError_t launch_quant_in(const int32_t* S, int npix, int C, const int32_t* idx, int n_a, int M, int s, int8_t* xq,
-                           int cpad, hipStream_t st);
+// 8-bit codes of the first n_a logical channels (physical idx[c]) of state S [npix][C], npix =
+// batch * h * w. xq holds cpad channels (multiple of 64) in 64-channel planes of zero-bordered
+// images, `plane` bytes apart; channels >= n_a are written as 0, borders are left alone.
+hipError_t launch_quant_in(const int32_t* S, int npix, int h, int w, int C, const int32_t* idx, int n_a, int M, int s,
+                           int8_t* xq, int cpad, long long plane, hipStream_t st);
 // Split: logical channels >= c_keep go to z (chunk at zoff, image stride d); channels < c_keep
 // are squeezed into Snext [B][h/2][w/2][4*c_keep]. c_keep = 0 emits everything (last level).
 hipError_t launch_factor_out(const int32_t* S, int B, int h, int w, int C, const int32_t* phi, int c_keep, int32_t* z,

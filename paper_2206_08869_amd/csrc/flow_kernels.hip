@@ -56,24 +56,28 @@ __device__ __forceinline__ int rq_in(int a, int M, int s) {
 }
 
 // Codes of channel c < n_a of pixel p: sat8(rq(S[p][idx[c]]; M, s)); channels n_a..cpad-1 are 0.
-// xq is laid out in 64-channel planes: xq[(c / 64) * npix * 64 + p * 64 + c % 64]. One thread per 4 channels.
-__global__ void k_quant_in(const int32_t* __restrict__ S, int npix, int C, const int32_t* __restrict__ idx, int n_a,
-                           int M, int s, int8_t* __restrict__ xq, int cpad) {
+// xq is laid out in 64-channel planes of zero-bordered images (see conv.h): channel c of pixel
+// (b, i, j) at xq[(c / 64) * plane + pos(b, i, j) * 64 + c % 64]. One thread per 4 channels.
+__global__ void k_quant_in(const int32_t* __restrict__ S, int npix, int h, int w, int C, const int32_t* __restrict__ idx,
+                           int n_a, int M, int s, int8_t* __restrict__ xq, int cpad, long long plane) {
     const int groups = cpad / 4;
     const long long n = (long long)npix * groups;
+    const int hw = h * w, W2 = w + 2, PP = (h + 2) * W2;
     for (long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x; t < n; t += (long long)gridDim.x * blockDim.x) {
         const int g = (int)(t % groups);
-        const long long p = t / groups;
+        const int p = (int)(t / groups);
         unsigned packed = 0;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int c = g * 4 + e;
             int v = 0;
-            if (c < n_a) v = rq_in(S[p * C + idx[c]], M, s);
+            if (c < n_a) v = rq_in(S[(long long)p * C + idx[c]], M, s);
             packed |= ((unsigned)v & 0xffu) << (8 * e);
         }
         const int c0 = g * 4;
-        *(unsigned*)(xq + ((long long)(c0 >> 6) * npix + p) * 64 + (c0 & 63)) = packed;
+        const int b = p / hw, q = p - b * hw, i = q / w, j = q - i * w;
+        const long long pos = (long long)b * PP + (i + 1) * W2 + (j + 1);
+        *(unsigned*)(xq + (long long)(c0 >> 6) * plane + pos * 64 + (c0 & 63)) = packed;
     }
 }
 
@@ -145,12 +149,14 @@ hipError_t launch_emit_x(const int32_t* s1, int B, int H, int W, uint8_t* x, uns
     return hipGetLastError();
 }
 
-hipError_t launch_quant_in(const int32_t* S, int npix, int C, const int32_t* idx, int n_a, int M, int s, int8_t* xq,
-                           int cpad, hipStream_t st) {
+hipError_t launch_quant_in(const int32_t* S, int npix, int h, int w, int C, const int32_t* idx, int n_a, int M, int s,
+                           int8_t* xq, int cpad, long long plane, hipStream_t st) {
     if (npix <= 0) return hipSuccess;
-    if (cpad % 64 || n_a > cpad) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(k_quant_in, dim3(grid_for((long long)npix * (cpad / 4))), dim3(TPB), 0, st, S, npix, C, idx, n_a,
-                       M, s, xq, cpad);
+    if (cpad % 64 || n_a > cpad || h < 1 || w < 1 || npix % (h * w) ||
+        plane < (long long)(npix / (h * w)) * (h + 2) * (w + 2) * 64)
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_quant_in, dim3(grid_for((long long)npix * (cpad / 4))), dim3(TPB), 0, st, S, npix, h, w, C, idx,
+                       n_a, M, s, xq, cpad, plane);
     return hipGetLastError();
 }
 

@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <array>
 #include <cstring>
 #include <new>
 #include <string>
@@ -410,11 +411,13 @@ struct iodf_ctx {
     long long d = 0, d_codes = 0;
     uint8_t* params = nullptr;        // packed weights, constants, index maps
     size_t params_bytes = 0;
-    int8_t* buf[NUM_BUFS] = {nullptr, nullptr, nullptr};
-    int buf_w[NUM_BUFS] = {0, 0, 0};
+    // Activation buffers per level (1-based): each level has its own image geometry, and the
+    // zero borders of its planes must never be overwritten by another geometry's pixels.
+    std::vector<std::array<int8_t*, NUM_BUFS>> buf;
+    std::vector<std::array<int, NUM_BUFS>> buf_w;   // channels (multiple of 64)
+    std::vector<long long> plane;                   // bytes between 64-channel planes = max_batch * (h+2)*(w+2) * 64
     std::vector<int32_t*> state;      // per level (1-based), int32 [B][h][w][C]
     unsigned long long* range_errs = nullptr;
-    int8_t* zeros = nullptr;          // 256 zero bytes: source of convolution padding
     size_t workspace_bytes = 0;
     long long macs_fwd = 0, macs_inv = 0, macs_wide = 0;
     int conv_launches = 0;
@@ -455,17 +458,17 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
     const int npix = batch * h * w;
     const int32_t* phi = (const int32_t*)(ctx->params + N.phi_off);
     const int ntile = conv_num_tiles();
+    const long long plane = ctx->plane[lv];
     PROF_LAUNCH(ctx, st, ntile + CLS_QUANT_IN, 0, (long long)npix * (4 * N.C_in + N.cin_pad0),
-                launch_quant_in(ctx->state[lv], npix, N.C, phi, N.C_in, N.M_in, N.s_in, ctx->buf[BUF_XQ], N.cin_pad0, st));
-    if (N.zero_a)
+                launch_quant_in(ctx->state[lv], npix, h, w, N.C, phi, N.C_in, N.M_in, N.s_in, ctx->buf[lv][BUF_XQ],
+                                N.cin_pad0, plane, st));
+    if (N.zero_a)  // whole planes of the residual stream; zeroing borders again is harmless
         PROF_LAUNCH(ctx, st, ntile + CLS_FILL_ZERO, 0, (long long)npix * N.a_stride,
-                    launch_fill_zero(ctx->buf[BUF_A], (size_t)npix * N.a_stride, st));
+                    launch_fill_zero(ctx->buf[lv][BUF_A], (size_t)plane * (N.a_stride / 64), st));
     for (const DevLayer& L : N.layers) {
         ConvArgs a;
         memset(&a, 0, sizeof(a));
-        const long long plane = (long long)npix * 64;  // bytes between 64-channel planes in every buffer
-        a.in = ctx->buf[L.in_buf];
-        a.zeros = ctx->zeros;
+        a.in = ctx->buf[lv][L.in_buf];
         a.in_plane = plane;
         a.in_chunk0 = L.in_off / 64;
         a.cin_pad = L.cin_pad;
@@ -481,7 +484,7 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
         a.mode = L.mode;
         a.relu = L.relu;
         if (L.mode == MODE_ACT) {
-            a.out = ctx->buf[L.out_buf];
+            a.out = ctx->buf[lv][L.out_buf];
             a.out_plane = plane;
             a.out_chunk0 = L.out_off / 64;
             a.out_map = L.map_off == (size_t)-1 ? nullptr : (const int32_t*)(ctx->params + L.map_off);
@@ -571,6 +574,9 @@ int iodf_init(iodf_ctx** out, const void* model_blob, size_t blob_bytes, int dev
     Arena A;
     A.host.reserve(blob_bytes + blob_bytes / 2 + (1 << 20));
     ctx->nets.resize(hm.nets.size());
+    ctx->buf.assign(hm.levels + 2, std::array<int8_t*, NUM_BUFS>{nullptr, nullptr, nullptr});
+    ctx->buf_w.assign(hm.levels + 2, std::array<int, NUM_BUFS>{0, 0, 0});
+    ctx->plane.assign(hm.levels + 2, 0);
     {
         size_t n = 0;
         for (int lv = 1; lv <= hm.levels; ++lv) {
@@ -585,11 +591,11 @@ int iodf_init(iodf_ctx** out, const void* model_blob, size_t blob_bytes, int dev
                 last_off = A.alloc(4 * (size_t)C);
                 memcpy(A.host.data() + last_off, phi.data(), 4 * (size_t)C);
                 ctx->nets[n].phi_off = last_off;
-                plan_net(A, hm, hm.nets[n], ctx->nets[n], ctx->buf_w);
+                plan_net(A, hm, hm.nets[n], ctx->nets[n], ctx->buf_w[lv].data());
             }
             if (hm.has_heads && lv < hm.levels) {
                 ctx->nets[n].phi_off = last_off;
-                plan_net(A, hm, hm.nets[n], ctx->nets[n], ctx->buf_w);
+                plan_net(A, hm, hm.nets[n], ctx->nets[n], ctx->buf_w[lv].data());
                 ++n;
             }
         }
@@ -623,10 +629,18 @@ int iodf_init(iodf_ctx** out, const void* model_blob, size_t blob_bytes, int dev
         e = hipMemcpy(ctx->params, A.host.data(), ctx->params_bytes, hipMemcpyHostToDevice);
         if (e != hipSuccess) { g_last_hip = (int)e; ok = false; }
     }
-    for (int b = 0; b < NUM_BUFS && ok; ++b) {
-        const size_t bytes = (size_t)px1 * (size_t)std::max(ctx->buf_w[b], 64);
-        ok = dev_alloc((void**)&ctx->buf[b], bytes);
-        if (ok) { e = hipMemset(ctx->buf[b], 0, bytes); if (e != hipSuccess) { g_last_hip = (int)e; ok = false; } }
+    for (int lv = 1; lv <= hm.levels && ok; ++lv) {
+        const long long pp = (long long)((hm.H >> lv) + 2) * ((hm.W >> lv) + 2);
+        ctx->plane[lv] = ((long long)max_batch * pp * 64 + 1023) / 1024 * 1024;
+        if (ctx->plane[lv] >= (1LL << 31)) { iodf_free(ctx); return IODF_E_BATCH; }
+        for (int b = 0; b < NUM_BUFS && ok; ++b) {
+            const size_t bytes = (size_t)ctx->plane[lv] * (size_t)(std::max(ctx->buf_w[lv][b], 64) / 64);
+            ok = dev_alloc((void**)&ctx->buf[lv][b], bytes);
+            if (ok) {  // the borders (and everything else) start as zeros
+                e = hipMemset(ctx->buf[lv][b], 0, bytes);
+                if (e != hipSuccess) { g_last_hip = (int)e; ok = false; }
+            }
+        }
     }
     ctx->state.assign(hm.levels + 2, nullptr);
     for (int lv = 1; lv <= hm.levels && ok; ++lv) {
@@ -634,10 +648,8 @@ int iodf_init(iodf_ctx** out, const void* model_blob, size_t blob_bytes, int dev
         ok = dev_alloc((void**)&ctx->state[lv], bytes);
     }
     ok = ok && dev_alloc((void**)&ctx->range_errs, sizeof(unsigned long long));
-    ok = ok && dev_alloc((void**)&ctx->zeros, 256);
     if (ok) {
-        e = hipMemset(ctx->zeros, 0, 256);
-        if (e == hipSuccess) e = hipMemset(ctx->range_errs, 0, sizeof(unsigned long long));
+        e = hipMemset(ctx->range_errs, 0, sizeof(unsigned long long));
         if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e != hipSuccess) { g_last_hip = (int)e; ok = false; }
     }
@@ -654,12 +666,12 @@ void iodf_free(iodf_ctx* ctx) {
     if (!ctx) return;
     (void)hipSetDevice(ctx->device);
     if (ctx->params) (void)hipFree(ctx->params);
-    for (int b = 0; b < NUM_BUFS; ++b)
-        if (ctx->buf[b]) (void)hipFree(ctx->buf[b]);
+    for (auto& lvbuf : ctx->buf)
+        for (int8_t* b : lvbuf)
+            if (b) (void)hipFree(b);
     for (int32_t* s : ctx->state)
         if (s) (void)hipFree(s);
     if (ctx->range_errs) (void)hipFree(ctx->range_errs);
-    if (ctx->zeros) (void)hipFree(ctx->zeros);
     for (hipEvent_t& e : ctx->prof_ev)
         if (e) (void)hipEventDestroy(e);
     delete ctx;
