@@ -233,7 +233,7 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
     constexpr int STAGE = (BC + BP) * KT;
     static_assert(WTC % 32 == 0 && WTP % 32 == 0, "wave tile must be a multiple of 32x32");
     static_assert(BC % (16 * NW) == 0 && BP % (16 * NW) == 0, "tile rows must divide over the waves");
-    static_assert(NST >= 4 && (NST - 2) * LPT < 64, "pipeline depth must fit the vmcnt counter");
+    static_assert(NST >= 3 && (NST - 2) * LPT < 64, "pipeline depth must fit the vmcnt counter");
 
     extern __shared__ __align__(1024) unsigned char lds[];
 
@@ -296,26 +296,44 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
 
     typedef const void __attribute__((address_space(1))) * gptr_t;
     typedef void __attribute__((address_space(3))) * lptr_t;
-    // Next tile to issue: (itap, icc), all scalar. Past the last tile the last one is loaded
-    // again into a stage nobody reads, which keeps the number of loads per step constant.
-    int itap = 0, icc = 0, itile = 0;
+    // Next tile to issue. Its two source pointers are wave-uniform and advance by scalar
+    // additions only: weights by one k-tile, activations by one 64-channel plane, and at a tap
+    // change by the shift to the next tap (+1 pixel, or to the start of the next kernel row)
+    // minus the planes walked. Past the last tile the last one is loaded again into a stage
+    // nobody reads, which keeps the number of loads per step constant.
+    int itile = 0, icc = 0, ikx = 0;
+    const int8_t* wt = wbase;
+    const int8_t* at = abase + (a.taps == 9 ? -(long long)(W2 + 1) * KT : 0LL);  // tap (0,0) is pixel (i-1, j-1)
+    const long long tap_back = (long long)(cpt - 1) * a.in_plane;
+    auto uniform = [](const int8_t* p) {  // tell the compiler the pointer sits in SGPRs
+        const unsigned long long v = (unsigned long long)p;
+        const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+        const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+        return (const int8_t*)(((unsigned long long)hi << 32) | lo);
+    };
     auto issue = [&]() {
         unsigned char* sb = lds + (itile % NST) * STAGE;
-        const int8_t* wt = wbase + (long long)(itap * cpt + icc) * wtile;
+        const int8_t* wu = uniform(wt);
+        const int8_t* au = uniform(at);
 #pragma unroll
         for (int u = 0; u < WI; ++u)
-            __builtin_amdgcn_global_load_lds((gptr_t)(wt + u * 1024 + woffl), (lptr_t)(sb + (wave * WI + u) * 1024), 16,
+            __builtin_amdgcn_global_load_lds((gptr_t)(wu + u * 1024 + woffl), (lptr_t)(sb + (wave * WI + u) * 1024), 16,
                                              0, 0);
-        // tap (ky, kx) reads the pixel at (i + ky - 1, j + kx - 1): a constant shift in the
-        // bordered plane, and the border supplies the zero padding
-        const int dpix = a.taps == 9 ? (itap / 3 - 1) * W2 + (itap % 3 - 1) : 0;
-        const int8_t* at = abase + (long long)icc * a.in_plane + (long long)dpix * KT;
 #pragma unroll
         for (int u = 0; u < AI; ++u)
-            __builtin_amdgcn_global_load_lds((gptr_t)(at + aoffl[u]), (lptr_t)(sb + BC * KT + (wave * AI + u) * 1024),
+            __builtin_amdgcn_global_load_lds((gptr_t)(au + aoffl[u]), (lptr_t)(sb + BC * KT + (wave * AI + u) * 1024),
                                              16, 0, 0);
         ++itile;
-        if (itile < nkt && ++icc == cpt) { icc = 0; ++itap; }
+        if (itile < nkt) {
+            wt += wtile;
+            if (++icc == cpt) {
+                icc = 0;
+                at += (long long)(ikx == 2 ? W2 - 2 : 1) * KT - tap_back;
+                ikx = ikx == 2 ? 0 : ikx + 1;
+            } else {
+                at += a.in_plane;
+            }
+        }
     };
 
 #pragma unroll
@@ -351,10 +369,14 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
     for (int kt = 0; kt < nkt; ++kt) {
         const int st = kt % NST;
         read_frags(st, 1, wf1, af1);
-        mma(wf0, af0);
-        // Tile kt+1 has landed for everybody, and everybody is past its reads of tile kt-1,
-        // whose stage the next issue overwrites. (Past the end the tiles are zero fill.)
+        // Everybody is past its reads of tile kt-1 (they returned before the last barrier), so
+        // its stage can take tile kt+NST-1. The address arithmetic goes before this step's
+        // matrix work: a wave that has queued its MFMAs then reaches the barrier at once, and
+        // the other wave of the SIMD keeps the matrix core busy meanwhile.
         issue();
+        __builtin_amdgcn_sched_barrier(0);
+        mma(wf0, af0);
+        // tile kt+1 has landed for everybody
         wait_tiles_then_barrier<(NST - 2) * LPT>();
         read_frags((kt + 1) % NST, 0, wf0, af0);
         mma(wf1, af1);
@@ -388,8 +410,6 @@ struct TileCfg {
 
 const TileCfg kTiles[] = {
     IODF_TILE(256, 256, 2, 4, 4),
-    IODF_TILE(256, 256, 4, 2, 4),
-    IODF_TILE(256, 256, 2, 2, 4),
     IODF_TILE(128, 128, 2, 2, 4),
     IODF_TILE(64, 256, 1, 4, 4),
     IODF_TILE(64, 64, 2, 2, 4),
