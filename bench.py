@@ -31,6 +31,8 @@ def main():
     ap.add_argument("--direction", default="forward", choices=["forward", "inverse"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="only run a plain 1 GiB device copy (calibrates HBM byte counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (images are independent; a multi-GPU run would "
@@ -39,6 +41,14 @@ def main():
 
     import numpy as np
     import torch
+    if args.copy_probe:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": 1 << 30, "copy_probe_bytes_written": 1 << 30, "copies": 3}))
+        return
     import paper_2206_08869_amd as iodf
     from synth import CONFIGS, make_blob, make_images
 

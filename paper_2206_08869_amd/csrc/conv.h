@@ -28,7 +28,8 @@ struct ConvArgs {
     int taps;      // 1 (1x1) or 9 (3x3, pad 1, stride 1)
     int h, w;      // feature map size
     int npix;      // batch * h * w
-    // weights: int8 [taps * cin_pad / 64][n_pad][64]: k-tile major, so a [channels][64] tile is contiguous
+    // weights: int8 [cin_pad / 64][taps][n_pad][64]: k-tile major (64-channel plane, then tap), so a
+    // [channels][64] tile is contiguous and the taps of one plane follow each other
     const int8_t* wgt;
     int n_pad;     // multiple of 64; rows n >= true C_out are zero
     // per output channel constants, length n_pad

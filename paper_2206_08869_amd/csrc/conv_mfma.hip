@@ -296,15 +296,16 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
 
     typedef const void __attribute__((address_space(1))) * gptr_t;
     typedef void __attribute__((address_space(3))) * lptr_t;
-    // Next tile to issue. Its two source pointers are wave-uniform and advance by scalar
-    // additions only: weights by one k-tile, activations by one 64-channel plane, and at a tap
-    // change by the shift to the next tap (+1 pixel, or to the start of the next kernel row)
-    // minus the planes walked. Past the last tile the last one is loaded again into a stage
-    // nobody reads, which keeps the number of loads per step constant.
-    int itile = 0, icc = 0, ikx = 0;
+    // Next tile to issue. K runs plane-major, tap-minor: the nine taps of one 64-channel plane
+    // are consecutive k-tiles, so they re-read almost the same cache lines back to back. Both
+    // source pointers are wave-uniform and advance by scalar additions only: weights by one
+    // k-tile; activations by the shift to the next tap (+1 pixel, or to the start of the next
+    // kernel row), and after the last tap to tap (0,0) of the next plane. Past the last tile the
+    // last one is loaded again into a stage nobody reads, which keeps the loads per step constant.
+    int itile = 0, itap = 0, ikx = 0;
     const int8_t* wt = wbase;
     const int8_t* at = abase + (a.taps == 9 ? -(long long)(W2 + 1) * KT : 0LL);  // tap (0,0) is pixel (i-1, j-1)
-    const long long tap_back = (long long)(cpt - 1) * a.in_plane;
+    const long long next_plane = a.in_plane - (a.taps == 9 ? (long long)(2 * W2 + 2) * KT : 0LL);
     auto uniform = [](const int8_t* p) {  // tell the compiler the pointer sits in SGPRs
         const unsigned long long v = (unsigned long long)p;
         const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
@@ -326,12 +327,13 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
         ++itile;
         if (itile < nkt) {
             wt += wtile;
-            if (++icc == cpt) {
-                icc = 0;
-                at += (long long)(ikx == 2 ? W2 - 2 : 1) * KT - tap_back;
-                ikx = ikx == 2 ? 0 : ikx + 1;
+            if (++itap == a.taps) {
+                itap = 0;
+                ikx = 0;
+                at += next_plane;
             } else {
-                at += a.in_plane;
+                at += (ikx == 2 ? W2 - 2 : 1) * KT;
+                ikx = ikx == 2 ? 0 : ikx + 1;
             }
         }
     };

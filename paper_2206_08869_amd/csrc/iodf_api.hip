@@ -259,14 +259,12 @@ void pack_layer(Arena& A, const HostLayer& L, const std::vector<int>& rows, cons
     for (size_t n = 0; n < rows.size(); ++n) {
         const int r = rows[n];
         const int8_t* src = L.W + (size_t)r * L.C_in * taps;
-        // k = t * cin_pad + pc; element (n, k) goes to tile k / 64, row n, byte k % 64
+        // input column pc, tap t goes to k-tile (pc / 64) * taps + t, row n, byte pc % 64
         for (int c = 0; c < L.C_in; ++c) {
             const int pc = colpos[c];
             if (pc < 0) continue;
-            for (int t = 0; t < taps; ++t) {
-                const size_t k = (size_t)t * cin_pad + pc;
-                w[((k >> 6) * D.n_pad + n) * 64 + (k & 63)] = src[(size_t)c * taps + t];
-            }
+            for (int t = 0; t < taps; ++t)
+                w[(((size_t)(pc >> 6) * taps + t) * D.n_pad + n) * 64 + (pc & 63)] = src[(size_t)c * taps + t];
         }
         bias[n] = L.bias[r];
         mul[n] = L.M[r];
