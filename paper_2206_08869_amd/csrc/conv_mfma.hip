@@ -40,6 +40,9 @@ __device__ __forceinline__ void static_for(F&& f) {
 
 constexpr int KT = 64;    // bytes (= int8 values) of K per staged tile
 
+// Epilogue variants a kernel is compiled for.
+enum { EPI_ANY = 0, EPI_FAST = 1, EPI_FAST_RELU = 2 };
+
 // Round-half-away-from-zero of acc * M / 2^s, clamped far outside the 8-bit range
 // (the caller saturates to 8 bit after adding at most one 8-bit shortcut).
 __device__ __forceinline__ int rq_dev(int acc, int M, int s) {
@@ -65,7 +68,7 @@ __device__ __forceinline__ int rq_fast_abs(unsigned ua, int M, int sh) {
 // (register quads g = 0..3: channels g*8 + half*4 ..); three rounds of v_permlane32_swap
 // between the two wave halves regroup them into 16 consecutive channels per lane, stored
 // with one 16-byte write.
-template <int TC, int TP>
+template <int TC, int TP, bool PURE_RELU>
 __device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc)[TC][TP], const int pix_base,
                                                    const int ch_base, const int lane, const int hw) {
     const int half = lane >> 5, l32 = lane & 31;
@@ -79,7 +82,6 @@ __device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc
         const int b = m / hw, q = m - b * hw, i = q / a.w, j = q - i * a.w;
         ppos[tp] = (long long)(b * PP + (i + 1) * W2 + (j + 1)) * 64;
     }
-    const bool pure_relu = a.relu && !a.shortcut;
     static_for<TC>([&](auto tc_) {
         constexpr int tc = decltype(tc_)::value;
         v4i Mq[4], Sq[4];
@@ -100,8 +102,8 @@ __device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc
             static_for<4>([&](auto g_) {
                 constexpr int g = decltype(g_)::value;
                 int y[4];
-                if (pure_relu) {
-                    // negative accumulators end at 0 whatever their magnitude
+                if constexpr (PURE_RELU) {
+                    // ReLU without shortcut: negative accumulators end at 0 whatever their magnitude
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int av = acc[tc][tp][g * 4 + e];
@@ -223,7 +225,7 @@ __device__ __forceinline__ void wait_tiles_then_barrier() {
 // publishes it and frees the stage consumed before. Activation planes carry a one-pixel zero
 // border per image, so a 3x3 tap is a constant address shift and needs no bounds test; all
 // per-tile address arithmetic is scalar, the per-lane parts are computed once.
-template <int BC, int BP, int WC, int WP, int NST, bool FAST>
+template <int BC, int BP, int WC, int WP, int NST, int EPI>
 __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, const int npb, const int ncb) {
     constexpr int NW = WC * WP;
     constexpr int WTC = BC / WC, WTP = BP / WP;  // wave tile
@@ -386,8 +388,10 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
     // drain the tail loads (they target stages nobody reads any more) before the wave retires
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-    if constexpr (FAST)
-        conv_epilogue_fast<TC, TP>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw);
+    if constexpr (EPI == EPI_FAST_RELU)
+        conv_epilogue_fast<TC, TP, true>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw);
+    else if constexpr (EPI == EPI_FAST)
+        conv_epilogue_fast<TC, TP, false>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw);
     else
         conv_epilogue<TC, TP>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw);
 }
@@ -397,16 +401,17 @@ namespace {
 struct TileCfg {
     int bc, bp;
     size_t lds;
-    void (*kern_fast)(const ConvArgs, int, int);
-    void (*kern_any)(const ConvArgs, int, int);
+    void (*kern[3])(const ConvArgs, int, int);  // indexed by EPI_*
     int threads;
     const char* name;
 };
 
 #define IODF_TILE(BC, BP, WC, WP, NST)                                                              \
     TileCfg {                                                                                       \
-        BC, BP, (size_t)NST * (BC + BP) * KT, conv_igemm<BC, BP, WC, WP, NST, true>,                \
-            conv_igemm<BC, BP, WC, WP, NST, false>, WC * WP * 64,                                   \
+        BC, BP, (size_t)NST * (BC + BP) * KT,                                                       \
+            {conv_igemm<BC, BP, WC, WP, NST, EPI_ANY>, conv_igemm<BC, BP, WC, WP, NST, EPI_FAST>,   \
+             conv_igemm<BC, BP, WC, WP, NST, EPI_FAST_RELU>},                                       \
+            WC * WP * 64,                                                                           \
             "conv_igemm<" #BC "," #BP "," #WC "," #WP "," #NST ">"                                  \
     }
 
@@ -443,12 +448,11 @@ bool args_ok(const ConvArgs& a) {
 
 hipError_t conv_setup() {
     for (int i = 0; i < kNumTiles; ++i) {
-        hipError_t e = hipFuncSetAttribute((const void*)kTiles[i].kern_fast,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kTiles[i].lds);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void*)kTiles[i].kern_any, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)kTiles[i].lds);
-        if (e != hipSuccess) return e;
+        for (int v = 0; v < 3; ++v) {
+            hipError_t e = hipFuncSetAttribute((const void*)kTiles[i].kern[v],
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kTiles[i].lds);
+            if (e != hipSuccess) return e;
+        }
     }
     return hipSuccess;
 }
@@ -480,7 +484,8 @@ hipError_t launch_conv(const ConvArgs& a, hipStream_t stream) {
     const int npb = (a.npix + t.bp - 1) / t.bp, ncb = a.n_pad / t.bc;
     const int grid = ((npb + 7) / 8) * 8 * ncb;
     const bool fast = a.mode == MODE_ACT && !a.out_map && a.rq_fast && a.n_store % 16 == 0;
-    hipLaunchKernelGGL(fast ? t.kern_fast : t.kern_any, dim3(grid), dim3(t.threads), t.lds, stream, a, npb, ncb);
+    const int epi = !fast ? EPI_ANY : (a.relu && !a.shortcut) ? EPI_FAST_RELU : EPI_FAST;
+    hipLaunchKernelGGL(t.kern[epi], dim3(grid), dim3(t.threads), t.lds, stream, a, npb, ncb);
     return hipGetLastError();
 }
 
