@@ -19,6 +19,10 @@ if ROOT not in sys.path:
 
 INT8_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA peak, TOP/s
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the dominant kernel, from the two rocprofv3 --pmc runs summarised in
+# profiles/conv_hbm_traffic_cfg4.md (FETCH_SIZE x2.000 + WRITE_SIZE x1.000 against a 1 GiB copy).
+# Only valid for the workload it was measured on.
+PMC_TRAFFIC_BYTES = {("cfg4", 128, "conv_igemm<256,256,2,4,4>"): 198.4e6}
 
 
 def main():
@@ -117,7 +121,10 @@ def main():
         dom = max((s for s in stats if s["macs"]), key=lambda s: s["total_ms"])
         achieved = 2.0 * dom["macs"] / (dom["total_ms"] * 1e-3) / 1e12
         roofline = dict(bound="mfma", kernel=dom["name"], achieved=round(achieved, 2), peak=INT8_PEAK_TOPS,
-                        unit="TOP/s", frac=round(achieved / INT8_PEAK_TOPS, 4), traffic=None,
+                        unit="TOP/s", frac=round(achieved / INT8_PEAK_TOPS, 4),
+                        traffic=PMC_TRAFFIC_BYTES.get((cfg.name, batch, dom["name"])),
+                        algorithmic_bytes_per_launch=round(dom["bytes"] / dom["launches"]),
+                        algorithmic_ops_per_launch=round(2.0 * dom["macs"] / dom["launches"]),
                         launches=dom["launches"], avg_launch_ms=round(dom["total_ms"] / dom["launches"], 5),
                         share_of_step=round(dom["total_ms"] / (1e3 * elapsed), 4))
 
