@@ -37,6 +37,7 @@ struct ConvArgs {
     const int32_t* mul;
     const int32_t* shift;  // rq_fast: shift - 32 (every shift of the layer is >= 33); else the shift itself
     int rq_fast;
+    int32_t* partial;  // optional split-K scratch: int32 [npix][n_pad], all zero between launches
     int n_store;   // channels written (<= n_pad); multiple of 4 in MODE_ACT without out_map
     int mode;
     int relu;

@@ -203,6 +203,29 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs& a, v16i (&acc)[TC]
     });
 }
 
+// Split-K epilogue: add this workgroup's partial sums into the int32 scratch [pixel][n_pad].
+// Integer addition is associative, so the result does not depend on arrival order.
+template <int TC, int TP>
+__device__ __forceinline__ void conv_epilogue_partial(const ConvArgs& a, v16i (&acc)[TC][TP], const int pix_base,
+                                                      const int ch_base, const int lane) {
+    const int half = lane >> 5, l32 = lane & 31;
+    static_for<TP>([&](auto tp_) {
+        constexpr int tp = decltype(tp_)::value;
+        const int m = pix_base + tp * 32 + l32;
+        if (m >= a.npix) return;
+        static_for<TC>([&](auto tc_) {
+            constexpr int tc = decltype(tc_)::value;
+            static_for<4>([&](auto g_) {
+                constexpr int g = decltype(g_)::value;
+                const int nb = ch_base + tc * 32 + g * 8 + half * 4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (nb + e < a.n_store) atomicAdd(a.partial + (long long)m * a.n_pad + nb + e, acc[tc][tp][g * 4 + e]);
+            });
+        });
+    });
+}
+
 // Wait until at most N of this wave's global->LDS loads are outstanding and all of its LDS
 // reads have returned, then meet the other waves. Loads retire in order, so "at most N
 // outstanding" means every tile but the newest N / (loads per tile) has landed; the LDS-read
@@ -250,9 +273,13 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
     const int pb = (slot / ncb) * 8 + xcd, cb = slot % ncb;
     if (pb >= npb) return;
     const int p0 = pb * BP, c0 = cb * BC;
+    if (c0 >= a.n_store) return;  // a channel block of padding only
 
-    const int cpt = a.cin_pad / KT;  // k-tiles per tap
-    const int nkt = a.taps * cpt;
+    // split-K: blockIdx.y owns a contiguous range of k-tiles and adds its partial sums to a.partial
+    const int nkt_all = a.taps * (a.cin_pad / KT);
+    const int nsk = gridDim.y, sk = blockIdx.y;
+    const int kt0 = (int)((long long)nkt_all * sk / nsk);
+    const int nkt = (int)((long long)nkt_all * (sk + 1) / nsk) - kt0;
     const long long wtile = (long long)a.n_pad * KT;  // bytes per weight k-tile
     const int hw = a.h * a.w;
     const int W2 = a.w + 2, PP = (a.h + 2) * W2;  // zero-bordered image geometry
@@ -283,7 +310,8 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
         static_for<4>([&](auto g_) {
             constexpr int g = decltype(g_)::value;
             const int nb = c0 + wc * WTC + tc * 32 + g * 8 + half * 4;
-            const v4i b4 = *(const v4i*)(a.bias + nb);
+            v4i b4 = *(const v4i*)(a.bias + nb);
+            if (sk != 0) b4 = v4i{0, 0, 0, 0};  // the bias enters once
             static_for<TP>([&](auto tp_) {
                 constexpr int tp = decltype(tp_)::value;
                 acc[tc][tp][g * 4 + 0] = b4[0];
@@ -304,9 +332,11 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
     // k-tile; activations by the shift to the next tap (+1 pixel, or to the start of the next
     // kernel row), and after the last tap to tap (0,0) of the next plane. Past the last tile the
     // last one is loaded again into a stage nobody reads, which keeps the loads per step constant.
-    int itile = 0, itap = 0, ikx = 0;
-    const int8_t* wt = wbase;
-    const int8_t* at = abase + (a.taps == 9 ? -(long long)(W2 + 1) * KT : 0LL);  // tap (0,0) is pixel (i-1, j-1)
+    int itile = 0, itap = kt0 % a.taps, ikx = itap % 3;
+    const int8_t* wt = wbase + (long long)kt0 * wtile;
+    // tap (ky, kx) reads pixel (i + ky - 1, j + kx - 1)
+    const int8_t* at = abase + (long long)(kt0 / a.taps) * a.in_plane +
+                       (a.taps == 9 ? (long long)((itap / 3 - 1) * W2 + (ikx - 1)) * KT : 0LL);
     const long long next_plane = a.in_plane - (a.taps == 9 ? (long long)(2 * W2 + 2) * KT : 0LL);
     auto uniform = [](const int8_t* p) {  // tell the compiler the pointer sits in SGPRs
         const unsigned long long v = (unsigned long long)p;
@@ -327,17 +357,15 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
             __builtin_amdgcn_global_load_lds((gptr_t)(au + aoffl[u]), (lptr_t)(sb + BC * KT + (wave * AI + u) * 1024),
                                              16, 0, 0);
         ++itile;
-        if (itile < nkt) {
-            wt += wtile;
-            if (++itap == a.taps) {
-                itap = 0;
-                ikx = 0;
-                at += next_plane;
-            } else {
-                at += (ikx == 2 ? W2 - 2 : 1) * KT;
-                ikx = ikx == 2 ? 0 : ikx + 1;
-            }
-        }
+        // branch-free advance (selects on scalars); frozen once the last tile has been issued
+        const bool go = itile < nkt;
+        const bool wrap = itap + 1 == a.taps;
+        const bool row = ikx == 2;
+        const long long astep = wrap ? next_plane : (long long)((row ? W2 - 2 : 1) * KT);
+        wt += go ? wtile : 0LL;
+        at += go ? astep : 0LL;
+        itap = go ? (wrap ? 0 : itap + 1) : itap;
+        ikx = go ? ((wrap || row) ? 0 : ikx + 1) : ikx;
     };
 
 #pragma unroll
@@ -370,20 +398,28 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
     };
     wait_tiles_then_barrier<(NST - 2) * LPT>();  // tile 0 has landed
     read_frags(0, 0, wf0, af0);
-    for (int kt = 0; kt < nkt; ++kt) {
-        const int st = kt % NST;
+    // One step per k-tile. The steps are unrolled NST-fold so that every LDS stage offset is
+    // a compile-time constant.
+    auto step = [&](auto st_) {
+        constexpr int st = decltype(st_)::value;
         read_frags(st, 1, wf1, af1);
-        // Everybody is past its reads of tile kt-1 (they returned before the last barrier), so
-        // its stage can take tile kt+NST-1. The address arithmetic goes before this step's
-        // matrix work: a wave that has queued its MFMAs then reaches the barrier at once, and
-        // the other wave of the SIMD keeps the matrix core busy meanwhile.
-        issue();
-        __builtin_amdgcn_sched_barrier(0);
         mma(wf0, af0);
-        // tile kt+1 has landed for everybody
+        // Everybody is past its reads of tile kt-1 (they returned before the last barrier), so
+        // its stage can take tile kt+NST-1; then wait until tile kt+1 has landed for everybody.
+        issue();
         wait_tiles_then_barrier<(NST - 2) * LPT>();
-        read_frags((kt + 1) % NST, 0, wf0, af0);
+        read_frags((st + 1) % NST, 0, wf0, af0);
         mma(wf1, af1);
+    };
+    for (int kt = 0; kt < nkt; kt += NST) {
+        const int left = nkt - kt;
+        step(std::integral_constant<int, 0>{});
+        if (left > 1) step(std::integral_constant<int, 1>{});
+        if (left > 2) step(std::integral_constant<int, 2>{});
+        if constexpr (NST > 3) {
+            if (left > 3) step(std::integral_constant<int, 3>{});
+        }
+        static_assert(NST <= 4, "unrolled for at most four stages");
     }
     // drain the tail loads (they target stages nobody reads any more) before the wave retires
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -392,8 +428,40 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
         conv_epilogue_fast<TC, TP, true>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw);
     else if constexpr (EPI == EPI_FAST)
         conv_epilogue_fast<TC, TP, false>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw);
+    else if (nsk > 1)
+        conv_epilogue_partial<TC, TP>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane);
     else
         conv_epilogue<TC, TP>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw);
+}
+
+// Second phase of a split-K layer: requantise the summed accumulators, apply the layer's
+// mode, and leave the scratch zeroed for the next user. One thread per (pixel, channel).
+__global__ void conv_splitk_finish(const ConvArgs a) {
+    const int hw = a.h * a.w;
+    const long long n = (long long)a.npix * a.n_store;
+    for (long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x; t < n; t += (long long)gridDim.x * blockDim.x) {
+        const int m = (int)(t / a.n_store), c = (int)(t - (long long)m * a.n_store);
+        int32_t* ps = a.partial + (long long)m * a.n_pad + c;
+        const int av = *ps;
+        *ps = 0;
+        int y = rq_dev(av, a.mul[c], a.shift[c] + (a.rq_fast ? 32 : 0));
+        if (a.mode == MODE_ACT) {
+            const int ch = a.out_map ? a.out_map[c] : c;
+            const int bi = m / hw, qi = m - bi * hw, ii = qi / a.w, ji = qi - ii * a.w;
+            const long long pp = (long long)bi * ((a.h + 2) * (a.w + 2)) + (ii + 1) * (a.w + 2) + (ji + 1);
+            int8_t* o = a.out + (long long)(a.out_chunk0 + (ch >> 6)) * a.out_plane + pp * 64 + (ch & 63);
+            if (a.shortcut) y += (int)*o;
+            if (a.relu) y = y < 0 ? 0 : y;
+            *o = (int8_t)sat8_dev(y);
+        } else if (a.mode == MODE_COUPLE) {
+            if (a.relu) y = y < 0 ? 0 : y;
+            a.state[(long long)m * a.state_c + a.idx_b[c]] += a.sign * sat8_dev(y);
+        } else {
+            if (a.relu) y = y < 0 ? 0 : y;
+            const int b = m / hw, q = m - b * hw;
+            a.codes[(long long)b * a.codes_img_stride + a.codes_off + (long long)c * hw + q] = (int8_t)sat8_dev(y);
+        }
+    }
 }
 
 namespace {
@@ -469,11 +537,26 @@ int conv_pick_tile(const ConvArgs& a) {
     if (forced >= 0 && forced < kNumTiles && a.n_pad % kTiles[forced].bc == 0) return forced;
     for (int i = 0; i < kNumTiles; ++i) {
         if (a.n_pad % kTiles[i].bc) continue;
-        const long long blocks = (long long)((a.npix + kTiles[i].bp - 1) / kTiles[i].bp) * (a.n_pad / kTiles[i].bc);
+        const long long blocks = (long long)((a.npix + kTiles[i].bp - 1) / kTiles[i].bp) *
+                                 ((a.n_store + kTiles[i].bc - 1) / kTiles[i].bc);
         if (blocks >= 256) return i;
         if (blocks > best_blocks) { best_blocks = blocks; best = i; }
     }
     return best;
+}
+
+// K splits for a layer whose tiles alone cannot fill the chip (only the general epilogue
+// supports it, and only when the caller supplied the scratch).
+int conv_pick_splits(const ConvArgs& a, int tile) {
+    const bool fast = a.mode == MODE_ACT && !a.out_map && a.rq_fast && a.n_store % 16 == 0;
+    if (fast || !a.partial || tile < 0) return 1;
+    const TileCfg& t = kTiles[tile];
+    const long long blocks = (long long)((a.npix + t.bp - 1) / t.bp) * ((a.n_store + t.bc - 1) / t.bc);
+    const int nkt = a.taps * (a.cin_pad / KT);
+    long long s = 512 / (blocks > 0 ? blocks : 1);
+    if (s > nkt / 16) s = nkt / 16;
+    if (s > 32) s = 32;
+    return s < 2 ? 1 : (int)s;
 }
 
 hipError_t launch_conv(const ConvArgs& a, hipStream_t stream) {
@@ -485,7 +568,13 @@ hipError_t launch_conv(const ConvArgs& a, hipStream_t stream) {
     const int grid = ((npb + 7) / 8) * 8 * ncb;
     const bool fast = a.mode == MODE_ACT && !a.out_map && a.rq_fast && a.n_store % 16 == 0;
     const int epi = !fast ? EPI_ANY : (a.relu && !a.shortcut) ? EPI_FAST_RELU : EPI_FAST;
-    hipLaunchKernelGGL(t.kern[epi], dim3(grid), dim3(t.threads), t.lds, stream, a, npb, ncb);
+    const int splits = conv_pick_splits(a, best);
+    hipLaunchKernelGGL(t.kern[epi], dim3(grid, splits), dim3(t.threads), t.lds, stream, a, npb, ncb);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || splits == 1) return e;
+    const long long n = (long long)a.npix * a.n_store;
+    const int fgrid = (int)((n + 255) / 256 > 4096 ? 4096 : (n + 255) / 256);
+    hipLaunchKernelGGL(conv_splitk_finish, dim3(fgrid), dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 

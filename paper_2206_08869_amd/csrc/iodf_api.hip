@@ -416,6 +416,8 @@ struct iodf_ctx {
     std::vector<long long> plane;                   // bytes between 64-channel planes = max_batch * (h+2)*(w+2) * 64
     std::vector<int32_t*> state;      // per level (1-based), int32 [B][h][w][C]
     unsigned long long* range_errs = nullptr;
+    int32_t* partial = nullptr;       // split-K scratch of the last layers (zero between launches)
+    size_t partial_elems = 0;
     size_t workspace_bytes = 0;
     long long macs_fwd = 0, macs_inv = 0, macs_wide = 0;
     int conv_launches = 0;
@@ -479,6 +481,7 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
         a.shift = (const int32_t*)(ctx->params + L.shift_off);
         a.n_store = L.n_store;
         a.rq_fast = L.rq_fast;
+        if (L.mode != MODE_ACT && (size_t)npix * L.n_pad <= ctx->partial_elems) a.partial = ctx->partial;
         a.mode = L.mode;
         a.relu = L.relu;
         if (L.mode == MODE_ACT) {
@@ -646,6 +649,16 @@ int iodf_init(iodf_ctx** out, const void* model_blob, size_t blob_bytes, int dev
         ok = dev_alloc((void**)&ctx->state[lv], bytes);
     }
     ok = ok && dev_alloc((void**)&ctx->range_errs, sizeof(unsigned long long));
+    // split-K scratch: enough for the last layer of any network at full batch
+    for (const DevNet& N : ctx->nets) {
+        const size_t px = (size_t)max_batch * (hm.H >> N.level) * (hm.W >> N.level);
+        ctx->partial_elems = std::max(ctx->partial_elems, px * (size_t)N.layers.back().n_pad);
+    }
+    ok = ok && dev_alloc((void**)&ctx->partial, 4 * ctx->partial_elems);
+    if (ok) {
+        e = hipMemset(ctx->partial, 0, 4 * ctx->partial_elems);
+        if (e != hipSuccess) { g_last_hip = (int)e; ok = false; }
+    }
     if (ok) {
         e = hipMemset(ctx->range_errs, 0, sizeof(unsigned long long));
         if (e == hipSuccess) e = hipDeviceSynchronize();
@@ -670,6 +683,7 @@ void iodf_free(iodf_ctx* ctx) {
     for (int32_t* s : ctx->state)
         if (s) (void)hipFree(s);
     if (ctx->range_errs) (void)hipFree(ctx->range_errs);
+    if (ctx->partial) (void)hipFree(ctx->partial);
     for (hipEvent_t& e : ctx->prof_ev)
         if (e) (void)hipEventDestroy(e);
     delete ctx;
