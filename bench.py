@@ -35,6 +35,8 @@ def main():
     ap.add_argument("--direction", default="forward", choices=["forward", "inverse"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
+    ap.add_argument("--latency", action="store_true",
+                    help="also report p50/p90 ms per call over the timed steps (each call synchronised)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain 1 GiB device copy (calibrates HBM byte counters) and exit")
     args = ap.parse_args()
@@ -87,15 +89,35 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    if not args.no_profile:
-        flow.profile_begin(args.steps * (2 * launches + 256))
-    torch.cuda.synchronize()
+    # timed region: K steps, nothing else on the stream
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    stats = [] if args.no_profile else flow.profile_end()
+    # the same K steps again with every kernel bracketed by HIP events on the launch stream
+    # (per-kernel durations for the roofline; the events add gaps, so this pass is not `value`)
+    stats, prof_elapsed = [], None
+    if not args.no_profile:
+        flow.profile_begin(args.steps * (2 * launches + 256))
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        prof_elapsed = time.perf_counter() - t1
+        stats = flow.profile_end()
+    latency = None
+    if args.latency:
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for a, b in ev:
+            a.record()
+            step()
+            b.record()
+            torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in ev)
+        latency = {"p50_ms_per_call": round(ms[len(ms) // 2], 4), "p90_ms_per_call": round(ms[int(len(ms) * 0.9)], 4),
+                   "p50_ms_per_image": round(ms[len(ms) // 2] / batch, 4), "calls": len(ms)}
 
     # validity: the timed outputs decode back to the inputs exactly
     if args.direction == "forward":
@@ -126,7 +148,8 @@ def main():
                         algorithmic_bytes_per_launch=round(dom["bytes"] / dom["launches"]),
                         algorithmic_ops_per_launch=round(2.0 * dom["macs"] / dom["launches"]),
                         launches=dom["launches"], avg_launch_ms=round(dom["total_ms"] / dom["launches"], 5),
-                        share_of_step=round(dom["total_ms"] / (1e3 * elapsed), 4))
+                        share_of_step=round(dom["total_ms"] / (1e3 * elapsed), 4),
+                        instrumented_ms_per_step=round(1e3 * prof_elapsed / args.steps, 3))
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -161,6 +184,7 @@ def main():
         "whole_path_tops": round(whole_tops, 2),
         "whole_path_frac_of_int8_peak": round(whole_tops / INT8_PEAK_TOPS, 4),
         "round_trip_exact": round_trip,
+        "latency": latency,
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,

@@ -16,6 +16,10 @@
  * (NULL = the default stream). iodf_forward / iodf_inverse only enqueue work on
  * that stream and never synchronise; the caller synchronises before reading.
  * A context must not be used from two streams at once (it owns one workspace).
+ * Calls are replayed from HIP graphs kept per (direction, batch, with/without codes): the first
+ * call of a shape captures its graph on an internal stream (host work only, a few ms); inputs and
+ * outputs pass through internal staging buffers with device-to-device copies on the caller's
+ * stream. Setting IODF_NO_GRAPH=1 in the environment before iodf_init launches kernels directly.
  *
  * Every function returns IODF_OK (0) or a negative IODF_E_* code; nothing throws.
  */

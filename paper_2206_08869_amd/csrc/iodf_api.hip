@@ -7,6 +7,7 @@
 
 #include <algorithm>
 #include <array>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -421,6 +422,18 @@ struct iodf_ctx {
     size_t workspace_bytes = 0;
     long long macs_fwd = 0, macs_inv = 0, macs_wide = 0;
     int conv_launches = 0;
+    // Launch-bound shapes (small batches: ~650 dependent kernels per call) are replayed from a
+    // HIP graph. A graph is captured once per (direction, batch, codes) on an internal stream
+    // against internal staging buffers for x, z and codes; a call then is: copy in, graph
+    // launch, copy out, all on the caller's stream.
+    struct GraphEntry { int dir, batch, codes; hipGraphExec_t exec; unsigned long long last_use; };
+    std::vector<GraphEntry> graphs;
+    unsigned long long graph_clock = 0;
+    hipStream_t cap_stream = nullptr;
+    bool use_graphs = true;
+    uint8_t* stage_x = nullptr;
+    int32_t* stage_z = nullptr;
+    int8_t* stage_codes = nullptr;
     // optional per-launch timing (iodf_profile_begin / iodf_profile_end)
     struct ProfRec { int cls; long long macs, bytes; };
     bool prof_on = false;
@@ -649,6 +662,19 @@ int iodf_init(iodf_ctx** out, const void* model_blob, size_t blob_bytes, int dev
         ok = dev_alloc((void**)&ctx->state[lv], bytes);
     }
     ok = ok && dev_alloc((void**)&ctx->range_errs, sizeof(unsigned long long));
+    {
+        const char* ng = getenv("IODF_NO_GRAPH");
+        ctx->use_graphs = !(ng && ng[0] == '1');
+    }
+    if (ctx->use_graphs) {
+        ok = ok && dev_alloc((void**)&ctx->stage_x, (size_t)max_batch * ctx->d);
+        ok = ok && dev_alloc((void**)&ctx->stage_z, 4 * (size_t)max_batch * ctx->d);
+        ok = ok && dev_alloc((void**)&ctx->stage_codes, (size_t)max_batch * std::max<long long>(ctx->d_codes, 1));
+        if (ok) {
+            e = hipStreamCreateWithFlags(&ctx->cap_stream, hipStreamNonBlocking);
+            if (e != hipSuccess) { g_last_hip = (int)e; ok = false; }
+        }
+    }
     // split-K scratch: enough for the last layer of any network at full batch
     for (const DevNet& N : ctx->nets) {
         const size_t px = (size_t)max_batch * (hm.H >> N.level) * (hm.W >> N.level);
@@ -683,19 +709,19 @@ void iodf_free(iodf_ctx* ctx) {
     for (int32_t* s : ctx->state)
         if (s) (void)hipFree(s);
     if (ctx->range_errs) (void)hipFree(ctx->range_errs);
+    for (auto& g : ctx->graphs) (void)hipGraphExecDestroy(g.exec);
+    if (ctx->cap_stream) (void)hipStreamDestroy(ctx->cap_stream);
+    if (ctx->stage_x) (void)hipFree(ctx->stage_x);
+    if (ctx->stage_z) (void)hipFree(ctx->stage_z);
+    if (ctx->stage_codes) (void)hipFree(ctx->stage_codes);
     if (ctx->partial) (void)hipFree(ctx->partial);
     for (hipEvent_t& e : ctx->prof_ev)
         if (e) (void)hipEventDestroy(e);
     delete ctx;
 }
 
-int iodf_forward(iodf_ctx* ctx, const uint8_t* x_dev, int batch, int32_t* z_dev, int8_t* codes_dev, void* stream) {
-    if (!ctx) return IODF_E_ARG;
-    if (batch < 0 || batch > ctx->max_batch) return IODF_E_BATCH;
-    if (batch == 0) return IODF_OK;
-    if (!x_dev || !z_dev) return IODF_E_ARG;
-    hipStream_t st = (hipStream_t)stream;
-    HIP_TRY(hipSetDevice(ctx->device));
+static int enqueue_forward(iodf_ctx* ctx, const uint8_t* x_dev, int batch, int32_t* z_dev, int8_t* codes_dev,
+                           hipStream_t st) {
     const HostModel& m = ctx->shape;
     const int ntile = conv_num_tiles();
     PROF_LAUNCH(ctx, st, ntile + CLS_INGEST, 0, 5LL * batch * ctx->d,
@@ -720,13 +746,7 @@ int iodf_forward(iodf_ctx* ctx, const uint8_t* x_dev, int batch, int32_t* z_dev,
     return IODF_OK;
 }
 
-int iodf_inverse(iodf_ctx* ctx, const int32_t* z_dev, int batch, uint8_t* x_dev, void* stream) {
-    if (!ctx) return IODF_E_ARG;
-    if (batch < 0 || batch > ctx->max_batch) return IODF_E_BATCH;
-    if (batch == 0) return IODF_OK;
-    if (!x_dev || !z_dev) return IODF_E_ARG;
-    hipStream_t st = (hipStream_t)stream;
-    HIP_TRY(hipSetDevice(ctx->device));
+static int enqueue_inverse(iodf_ctx* ctx, const int32_t* z_dev, int batch, uint8_t* x_dev, hipStream_t st) {
     const HostModel& m = ctx->shape;
     for (int lv = m.levels; lv >= 1; --lv) {
         const int C = level_channels(lv), h = m.H >> lv, w = m.W >> lv;
@@ -743,6 +763,79 @@ int iodf_inverse(iodf_ctx* ctx, const int32_t* z_dev, int batch, uint8_t* x_dev,
     }
     PROF_LAUNCH(ctx, st, conv_num_tiles() + CLS_EMIT_X, 0, 5LL * batch * ctx->d,
                 launch_emit_x(ctx->state[1], batch, m.H, m.W, x_dev, ctx->range_errs, st));
+    return IODF_OK;
+}
+
+// Find or capture the graph of one call shape. Returns nullptr (and *rc) when capture fails.
+static hipGraphExec_t get_graph(iodf_ctx* ctx, int dir, int batch, int codes, int* rc) {
+    *rc = IODF_OK;
+    for (auto& g : ctx->graphs)
+        if (g.dir == dir && g.batch == batch && g.codes == codes) {
+            g.last_use = ++ctx->graph_clock;
+            return g.exec;
+        }
+    hipError_t e = hipStreamBeginCapture(ctx->cap_stream, hipStreamCaptureModeThreadLocal);
+    if (e != hipSuccess) { g_last_hip = (int)e; *rc = IODF_E_HIP; return nullptr; }
+    const int erc = dir == 0 ? enqueue_forward(ctx, ctx->stage_x, batch, ctx->stage_z, codes ? ctx->stage_codes : nullptr,
+                                               ctx->cap_stream)
+                             : enqueue_inverse(ctx, ctx->stage_z, batch, ctx->stage_x, ctx->cap_stream);
+    hipGraph_t graph = nullptr;
+    e = hipStreamEndCapture(ctx->cap_stream, &graph);
+    if (erc != IODF_OK || e != hipSuccess || !graph) {
+        if (graph) (void)hipGraphDestroy(graph);
+        if (e != hipSuccess) g_last_hip = (int)e;
+        *rc = erc != IODF_OK ? erc : IODF_E_HIP;
+        return nullptr;
+    }
+    hipGraphExec_t exec = nullptr;
+    e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    if (e != hipSuccess) { g_last_hip = (int)e; *rc = IODF_E_HIP; return nullptr; }
+    if (ctx->graphs.size() >= 8) {  // drop the least recently used shape
+        size_t victim = 0;
+        for (size_t i = 1; i < ctx->graphs.size(); ++i)
+            if (ctx->graphs[i].last_use < ctx->graphs[victim].last_use) victim = i;
+        (void)hipGraphExecDestroy(ctx->graphs[victim].exec);
+        ctx->graphs.erase(ctx->graphs.begin() + (long)victim);
+    }
+    ctx->graphs.push_back({dir, batch, codes, exec, ++ctx->graph_clock});
+    return exec;
+}
+
+int iodf_forward(iodf_ctx* ctx, const uint8_t* x_dev, int batch, int32_t* z_dev, int8_t* codes_dev, void* stream) {
+    if (!ctx) return IODF_E_ARG;
+    if (batch < 0 || batch > ctx->max_batch) return IODF_E_BATCH;
+    if (batch == 0) return IODF_OK;
+    if (!x_dev || !z_dev) return IODF_E_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipSetDevice(ctx->device));
+    if (!ctx->use_graphs || ctx->prof_on) return enqueue_forward(ctx, x_dev, batch, z_dev, codes_dev, st);
+    const int codes = (codes_dev && ctx->d_codes) ? 1 : 0;
+    int rc;
+    hipGraphExec_t exec = get_graph(ctx, 0, batch, codes, &rc);
+    if (!exec) return rc;
+    HIP_TRY(hipMemcpyAsync(ctx->stage_x, x_dev, (size_t)batch * ctx->d, hipMemcpyDeviceToDevice, st));
+    HIP_TRY(hipGraphLaunch(exec, st));
+    HIP_TRY(hipMemcpyAsync(z_dev, ctx->stage_z, 4 * (size_t)batch * ctx->d, hipMemcpyDeviceToDevice, st));
+    if (codes)
+        HIP_TRY(hipMemcpyAsync(codes_dev, ctx->stage_codes, (size_t)batch * ctx->d_codes, hipMemcpyDeviceToDevice, st));
+    return IODF_OK;
+}
+
+int iodf_inverse(iodf_ctx* ctx, const int32_t* z_dev, int batch, uint8_t* x_dev, void* stream) {
+    if (!ctx) return IODF_E_ARG;
+    if (batch < 0 || batch > ctx->max_batch) return IODF_E_BATCH;
+    if (batch == 0) return IODF_OK;
+    if (!x_dev || !z_dev) return IODF_E_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipSetDevice(ctx->device));
+    if (!ctx->use_graphs || ctx->prof_on) return enqueue_inverse(ctx, z_dev, batch, x_dev, st);
+    int rc;
+    hipGraphExec_t exec = get_graph(ctx, 1, batch, 0, &rc);
+    if (!exec) return rc;
+    HIP_TRY(hipMemcpyAsync(ctx->stage_z, z_dev, 4 * (size_t)batch * ctx->d, hipMemcpyDeviceToDevice, st));
+    HIP_TRY(hipGraphLaunch(exec, st));
+    HIP_TRY(hipMemcpyAsync(x_dev, ctx->stage_x, (size_t)batch * ctx->d, hipMemcpyDeviceToDevice, st));
     return IODF_OK;
 }
 

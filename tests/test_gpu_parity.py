@@ -120,3 +120,46 @@ def test_query_reports_algorithmic_macs():
         assert flow.query(iodf.IODF_Q_MACS_INVERSE) == macs_per_image(cfg, with_heads=False)
         assert flow.query(iodf.IODF_Q_Z_ELEMS) == cfg.d and flow.query(iodf.IODF_Q_CODE_BYTES) == cfg.d_codes
         flow.close()
+
+
+def test_graph_replay_equals_eager_launches(monkeypatch):
+    # Calls are replayed from a captured HIP graph. Replay each shape several times, with eager
+    # work and synchronisations in between, and compare every replay with the eager path.
+    import torch
+    name = "mini_dense_g"
+    cfg = CONFIGS[name]
+    monkeypatch.setenv("IODF_NO_GRAPH", "1")
+    eager = gpu_flow(name, max_batch=5)
+    monkeypatch.delenv("IODF_NO_GRAPH")
+    graph = gpu_flow(name, max_batch=5)
+    om = oracle_model(name)
+    x = images(name, batch=5)
+    xg = to_gpu(x)
+    z_ref, c_ref = om.forward(x)
+    for rep in range(4):
+        for b in (5, 2, 1, 5, 3):
+            xb = xg[:b].contiguous()
+            ze, ce = eager.forward(xb)
+            junk = torch.randn(1 << 16, device="cuda").sum()   # unrelated eager work between replays
+            zg, cg = graph.forward(xb)
+            torch.cuda.synchronize()
+            assert torch.equal(ze, zg) and torch.equal(ce, cg), (rep, b)
+            assert np.array_equal(zg.cpu().numpy(), z_ref[:b]) and np.array_equal(cg.cpu().numpy(), c_ref[:b])
+            xr = graph.inverse(zg)
+            zn, none = graph.forward(xb, want_codes=False)
+            torch.cuda.synchronize()
+            assert torch.equal(xr, xb) and torch.equal(zn, zg) and none is None
+            assert float(junk) == float(junk)
+    assert graph.range_errors() == 0
+    # more shapes than the cache holds: old graphs are dropped and recaptured on demand
+    big = gpu_flow(name, max_batch=12)
+    xs = to_gpu(images(name, batch=12))
+    outs = {}
+    for b in list(range(1, 13)) + [1, 2, 12]:
+        z, c = big.forward(xs[:b].contiguous())
+        torch.cuda.synchronize()
+        if b in outs:
+            assert torch.equal(outs[b], z)
+        outs[b] = z.clone()
+        assert torch.equal(z, outs[12][:b]) if 12 in outs else True
+    eager.close(); graph.close(); big.close()
