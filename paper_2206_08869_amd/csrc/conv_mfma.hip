@@ -70,7 +70,8 @@ __device__ __forceinline__ int rq_fast_abs(unsigned ua, int M, int sh) {
 // with one 16-byte write.
 template <int TC, int TP, bool PURE_RELU>
 __device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc)[TC][TP], const int pix_base,
-                                                   const int ch_base, const int lane, const int hw) {
+                                                   const int ch_base, const int lane, const int hw,
+                                                   const int* cst, const int cst_n, const int ch_local) {
     const int half = lane >> 5, l32 = lane & 31;
     const int W2 = a.w + 2, PP = (a.h + 2) * W2;
     // position of each of this lane's pixels in the zero-bordered plane
@@ -84,12 +85,13 @@ __device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc
     }
     static_for<TC>([&](auto tc_) {
         constexpr int tc = decltype(tc_)::value;
-        v4i Mq[4], Sq[4];
+        v4i Bq[4], Mq[4], Sq[4];  // bias, multiplier, shift - 32 of this lane's 16 channels (staged in LDS)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const int nb = ch_base + tc * 32 + g * 8 + half * 4;
-            Mq[g] = *(const v4i*)(a.mul + nb);
-            Sq[g] = *(const v4i*)(a.shift + nb);
+            const int nl = ch_local + tc * 32 + g * 8 + half * 4;
+            Bq[g] = *(const v4i*)(cst + nl);
+            Mq[g] = *(const v4i*)(cst + cst_n + nl);
+            Sq[g] = *(const v4i*)(cst + 2 * cst_n + nl);
         }
         static_for<TP>([&](auto tp_) {
             constexpr int tp = decltype(tp_)::value;
@@ -106,7 +108,7 @@ __device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc
                     // ReLU without shortcut: negative accumulators end at 0 whatever their magnitude
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const int av = acc[tc][tp][g * 4 + e];
+                        const int av = acc[tc][tp][g * 4 + e] + Bq[g][e];
                         const int r = rq_fast_abs((unsigned)(av < 0 ? 0 : av), Mq[g][e], Sq[g][e]);
                         y[e] = r > 127 ? 127 : r;
                     }
@@ -115,7 +117,7 @@ __device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc
                     if (a.shortcut && live) sc = *(const int*)(orow + g * 8 + half * 4);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const int av = acc[tc][tp][g * 4 + e];
+                        const int av = acc[tc][tp][g * 4 + e] + Bq[g][e];
                         const int sgn = av >> 31;
                         int r = rq_fast_abs((unsigned)((av ^ sgn) - sgn), Mq[g][e], Sq[g][e]);
                         r = (r ^ sgn) - sgn;
@@ -158,13 +160,14 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs& a, v16i (&acc)[TC]
                 constexpr int g = decltype(g_)::value;
                 const int nb = ch_base + tc * 32 + g * 8 + half * 4;
                 if (nb >= a.n_store) return;
+                const v4i B4 = *(const v4i*)(a.bias + nb);
                 const v4i M4 = *(const v4i*)(a.mul + nb);
                 const v4i S4 = *(const v4i*)(a.shift + nb) + (a.rq_fast ? 32 : 0);
                 int v[4];
-                v[0] = rq_dev(acc[tc][tp][g * 4 + 0], M4[0], S4[0]);
-                v[1] = rq_dev(acc[tc][tp][g * 4 + 1], M4[1], S4[1]);
-                v[2] = rq_dev(acc[tc][tp][g * 4 + 2], M4[2], S4[2]);
-                v[3] = rq_dev(acc[tc][tp][g * 4 + 3], M4[3], S4[3]);
+                v[0] = rq_dev(acc[tc][tp][g * 4 + 0] + B4[0], M4[0], S4[0]);
+                v[1] = rq_dev(acc[tc][tp][g * 4 + 1] + B4[1], M4[1], S4[1]);
+                v[2] = rq_dev(acc[tc][tp][g * 4 + 2] + B4[2], M4[2], S4[2]);
+                v[3] = rq_dev(acc[tc][tp][g * 4 + 3] + B4[3], M4[3], S4[3]);
                 if (a.mode == MODE_ACT) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -302,27 +305,27 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
     const int8_t* const wbase = a.wgt + (long long)(c0 + wave * WI * 16) * KT;
     const int8_t* const abase = a.in + (long long)a.in_chunk0 * a.in_plane;
 
-    // accumulators start at the 32-bit bias
+    // Accumulators start at zero; the 32-bit bias joins in the epilogue. The per-channel
+    // constants of this workgroup's BC channels are staged in LDS behind the stage ring (they
+    // become visible with the first barrier of the k loop), so the epilogue reads them with
+    // LDS latency and its loads do not queue behind the tile loads.
     v16i acc[TC][TP];
     const int half = lane >> 5, l32 = lane & 31;
     static_for<TC>([&](auto tc_) {
         constexpr int tc = decltype(tc_)::value;
-        static_for<4>([&](auto g_) {
-            constexpr int g = decltype(g_)::value;
-            const int nb = c0 + wc * WTC + tc * 32 + g * 8 + half * 4;
-            v4i b4 = *(const v4i*)(a.bias + nb);
-            if (sk != 0) b4 = v4i{0, 0, 0, 0};  // the bias enters once
-            static_for<TP>([&](auto tp_) {
-                constexpr int tp = decltype(tp_)::value;
-                acc[tc][tp][g * 4 + 0] = b4[0];
-                acc[tc][tp][g * 4 + 1] = b4[1];
-                acc[tc][tp][g * 4 + 2] = b4[2];
-                acc[tc][tp][g * 4 + 3] = b4[3];
-            });
+        static_for<TP>([&](auto tp_) {
+            constexpr int tp = decltype(tp_)::value;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[tc][tp][r] = 0;
         });
     });
-    // the bias loads must not be counted among the tile loads below
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    int* const cst = (int*)(lds + NST * STAGE);  // [3][BC]: bias, multiplier, shift
+    int cb_v = 0, cm_v = 0, cs_v = 0;
+    if (tid < BC) {
+        cb_v = a.bias[c0 + tid];
+        cm_v = a.mul[c0 + tid];
+        cs_v = a.shift[c0 + tid];
+    }
 
     typedef const void __attribute__((address_space(1))) * gptr_t;
     typedef void __attribute__((address_space(3))) * lptr_t;
@@ -370,6 +373,11 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
 
 #pragma unroll
     for (int t = 0; t < NST - 1; ++t) issue();
+    if (tid < BC) {
+        cst[tid] = cb_v;
+        cst[BC + tid] = cm_v;
+        cst[2 * BC + tid] = cs_v;
+    }
 
     // Fragment addresses inside a stage: row l32 of each 32-row tile, k-part (2*ks + half).
     // The loop is software pipelined: the fragments of the next 32-deep k-step are read from
@@ -425,9 +433,9 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     if constexpr (EPI == EPI_FAST_RELU)
-        conv_epilogue_fast<TC, TP, true>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw);
+        conv_epilogue_fast<TC, TP, true>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw, cst, BC, wc * WTC);
     else if constexpr (EPI == EPI_FAST)
-        conv_epilogue_fast<TC, TP, false>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw);
+        conv_epilogue_fast<TC, TP, false>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw, cst, BC, wc * WTC);
     else if (nsk > 1)
         conv_epilogue_partial<TC, TP>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane);
     else
@@ -442,7 +450,7 @@ __global__ void conv_splitk_finish(const ConvArgs a) {
     for (long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x; t < n; t += (long long)gridDim.x * blockDim.x) {
         const int m = (int)(t / a.n_store), c = (int)(t - (long long)m * a.n_store);
         int32_t* ps = a.partial + (long long)m * a.n_pad + c;
-        const int av = *ps;
+        const int av = *ps + a.bias[c];
         *ps = 0;
         int y = rq_dev(av, a.mul[c], a.shift[c] + (a.rq_fast ? 32 : 0));
         if (a.mode == MODE_ACT) {
@@ -476,7 +484,7 @@ struct TileCfg {
 
 #define IODF_TILE(BC, BP, WC, WP, NST)                                                              \
     TileCfg {                                                                                       \
-        BC, BP, (size_t)NST * (BC + BP) * KT,                                                       \
+        BC, BP, (size_t)NST * (BC + BP) * KT + 3 * BC * sizeof(int),                                 \
             {conv_igemm<BC, BP, WC, WP, NST, EPI_ANY>, conv_igemm<BC, BP, WC, WP, NST, EPI_FAST>,   \
              conv_igemm<BC, BP, WC, WP, NST, EPI_FAST_RELU>},                                       \
             WC * WP * 64,                                                                           \
