@@ -9,8 +9,27 @@ namespace iodf {
 enum ConvMode : int {
     MODE_ACT = 0,     // write 8-bit codes, pixel-major (NHWC), optionally + shortcut, ReLU
     MODE_COUPLE = 1,  // last layer of t(): state[b-half] += sign * sat8(rq(acc))   (Eq. 1)
-    MODE_CODES = 2    // last layer of a prior head: write int8 codes channel-first
+    MODE_CODES = 2,   // last layer of a prior head: write int8 codes channel-first
+    MODE_RAW = 3      // store the 32-bit accumulators (no bias, no requantise) to `partial` [npix][n_pad]
 };
+
+// Second phase of a tap-expanded 3x3 last layer. A 3x3 convolution with few output channels is
+// computed as ONE 1x1 GEMM with 9 * c_out rows (row t * c_out + c holds tap t of channel c; its
+// raw accumulators go to y), which reads the wide input once instead of nine times; this pass
+// then sums, for output pixel (i, j), the nine maps at their shifted positions
+//   acc[c](i, j) = sum_t y[(i + ky - 1, j + kx - 1)][t * c_out + c]   (zero outside the image)
+// adds the bias, requantises and applies the layer's mode (coupling add or head codes).
+struct TapSumArgs {
+    const int32_t* y;  // [npix][n_pad]
+    int n_pad, c_out, h, w, npix;
+    const int32_t* bias;   // [c_out]
+    const int32_t* mul;    // [c_out]
+    const int32_t* shift;  // [c_out], the full shift
+    int mode, relu;
+    int32_t* state; int state_c; const int32_t* idx_b; int sign;          // MODE_COUPLE
+    int8_t* codes; long long codes_img_stride; long long codes_off;       // MODE_CODES
+};
+hipError_t launch_tapsum(const TapSumArgs& a, hipStream_t stream);
 
 struct ConvArgs {
     // Activation tensors are int8 in 64-channel planes of zero-bordered images: pixel (b, i, j),

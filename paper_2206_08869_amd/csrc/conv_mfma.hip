@@ -160,6 +160,12 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs& a, v16i (&acc)[TC]
                 constexpr int g = decltype(g_)::value;
                 const int nb = ch_base + tc * 32 + g * 8 + half * 4;
                 if (nb >= a.n_store) return;
+                if (a.mode == MODE_RAW) {  // n_pad is a multiple of 64, so the quad is in bounds
+                    const v4i r4 = {acc[tc][tp][g * 4 + 0], acc[tc][tp][g * 4 + 1], acc[tc][tp][g * 4 + 2],
+                                    acc[tc][tp][g * 4 + 3]};
+                    *(v4i*)(a.partial + (long long)m * a.n_pad + nb) = r4;
+                    return;
+                }
                 const v4i B4 = *(const v4i*)(a.bias + nb);
                 const v4i M4 = *(const v4i*)(a.mul + nb);
                 const v4i S4 = *(const v4i*)(a.shift + nb) + (a.rq_fast ? 32 : 0);
@@ -517,7 +523,8 @@ bool args_ok(const ConvArgs& a) {
               (!a.out || a.out_plane < (long long)(a.npix / (a.h * a.w)) * (a.h + 2) * (a.w + 2) * KT ||
                a.out_plane % 64 || a.out_chunk0 < 0)) ||
              (a.mode == MODE_COUPLE && (!a.state || !a.idx_b || a.state_c < 1)) ||
-             (a.mode == MODE_CODES && !a.codes) || a.mode < MODE_ACT || a.mode > MODE_CODES);
+             (a.mode == MODE_CODES && !a.codes) || (a.mode == MODE_RAW && !a.partial) || a.mode < MODE_ACT ||
+             a.mode > MODE_RAW);
 }
 
 }  // namespace
@@ -556,6 +563,7 @@ int conv_pick_tile(const ConvArgs& a) {
 // K splits for a layer whose tiles alone cannot fill the chip (only the general epilogue
 // supports it, and only when the caller supplied the scratch).
 int conv_pick_splits(const ConvArgs& a, int tile) {
+    if (a.mode == MODE_RAW) return 1;  // its scratch is written, not accumulated
     const bool fast = a.mode == MODE_ACT && !a.out_map && a.rq_fast && a.n_store % 16 == 0;
     if (fast || !a.partial || tile < 0) return 1;
     const TileCfg& t = kTiles[tile];
@@ -583,6 +591,45 @@ hipError_t launch_conv(const ConvArgs& a, hipStream_t stream) {
     const long long n = (long long)a.npix * a.n_store;
     const int fgrid = (int)((n + 255) / 256 > 4096 ? 4096 : (n + 255) / 256);
     hipLaunchKernelGGL(conv_splitk_finish, dim3(fgrid), dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+namespace {
+
+__global__ void conv_tapsum(const TapSumArgs a) {
+    const int hw = a.h * a.w;
+    const long long n = (long long)a.npix * a.c_out;
+    for (long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x; t < n; t += (long long)gridDim.x * blockDim.x) {
+        const int m = (int)(t / a.c_out), c = (int)(t - (long long)m * a.c_out);
+        const int b = m / hw, q = m - b * hw, i = q / a.w, j = q - i * a.w;
+        int acc = a.bias[c];
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap) {
+            const int ii = i + tap / 3 - 1, jj = j + tap % 3 - 1;
+            if (ii >= 0 && ii < a.h && jj >= 0 && jj < a.w)
+                acc += a.y[((long long)b * hw + ii * a.w + jj) * a.n_pad + tap * a.c_out + c];
+        }
+        int y = rq_dev(acc, a.mul[c], a.shift[c]);
+        if (a.relu) y = y < 0 ? 0 : y;
+        y = sat8_dev(y);
+        if (a.mode == MODE_COUPLE)
+            a.state[(long long)m * a.state_c + a.idx_b[c]] += a.sign * y;
+        else
+            a.codes[(long long)b * a.codes_img_stride + a.codes_off + (long long)c * hw + q] = (int8_t)y;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_tapsum(const TapSumArgs& a, hipStream_t stream) {
+    if (a.npix <= 0) return hipSuccess;
+    if (!a.y || !a.bias || !a.mul || !a.shift || a.c_out < 1 || 9 * a.c_out > a.n_pad || a.h < 1 || a.w < 1 ||
+        a.npix % (a.h * a.w) || (a.mode == MODE_COUPLE && (!a.state || !a.idx_b)) ||
+        (a.mode == MODE_CODES && !a.codes) || (a.mode != MODE_COUPLE && a.mode != MODE_CODES))
+        return hipErrorInvalidValue;
+    const long long n = (long long)a.npix * a.c_out;
+    const int grid = (int)((n + 255) / 256 > 8192 ? 8192 : (n + 255) / 256);
+    hipLaunchKernelGGL(conv_tapsum, dim3(grid), dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -193,6 +193,10 @@ struct DevLayer {
     int out_buf, out_off;  // output tensor (MODE_ACT)
     size_t wgt_off, bias_off, mul_off, shift_off;  // byte offsets into the parameter arena
     size_t map_off;                                // (size_t)-1 when there is no scatter map
+    // tap-expanded 3x3 last layer (see TapSumArgs): the GEMM is 1x1 with 9 * c_out rows and
+    // stores raw accumulators; these are the constants of the summing pass
+    int expand_c_out = 0, final_mode = 0;
+    size_t fin_bias_off = 0, fin_mul_off = 0, fin_shift_off = 0;
     long long macs_per_pixel;                      // algorithmic: kept rows x live columns x taps
     long long bytes_per_pixel;                     // algorithmic: live input codes + kept output codes
     long long wgt_bytes;                           // algorithmic: kept rows x live columns x taps
@@ -285,6 +289,49 @@ void pack_layer(Arena& A, const HostLayer& L, const std::vector<int>& rows, cons
     D.wide = rows.size() >= 128 && live >= 128;
 }
 
+// Last layer of a network, 3x3 with few output channels, as a 1x1 GEMM over 9 * C_out rows.
+void pack_last_expanded(Arena& A, const HostLayer& L, const std::vector<int>& colpos, int cin_pad, int final_mode,
+                        DevLayer& D) {
+    const int co = L.C_out, rows = 9 * co;
+    D.taps = 1;
+    D.cin_pad = cin_pad;
+    D.n_pad = round64(rows);
+    D.n_store = rows;
+    D.relu = L.relu;
+    D.shortcut = 0;
+    D.map_off = (size_t)-1;
+    D.rq_fast = 0;
+    D.mode = MODE_RAW;
+    D.expand_c_out = co;
+    D.final_mode = final_mode;
+    D.wgt_off = A.alloc((size_t)D.n_pad * cin_pad);
+    D.bias_off = A.alloc(4 * (size_t)D.n_pad);   // unused by the raw GEMM, kept valid
+    D.mul_off = A.alloc(4 * (size_t)D.n_pad);
+    D.shift_off = A.alloc(4 * (size_t)D.n_pad);
+    D.fin_bias_off = A.alloc(4 * (size_t)co);
+    D.fin_mul_off = A.alloc(4 * (size_t)co);
+    D.fin_shift_off = A.alloc(4 * (size_t)co);
+    int8_t* w = (int8_t*)(A.host.data() + D.wgt_off);
+    int live = 0;
+    for (int c = 0; c < L.C_in; ++c) live += colpos[c] >= 0;
+    for (int r = 0; r < co; ++r)
+        for (int c = 0; c < L.C_in; ++c) {
+            const int pc = colpos[c];
+            if (pc < 0) continue;
+            for (int t = 0; t < 9; ++t)
+                w[((size_t)(pc >> 6) * D.n_pad + (size_t)(t * co + r)) * 64 + (pc & 63)] =
+                    L.W[((size_t)r * L.C_in + c) * 9 + t];
+        }
+    int32_t* fb = (int32_t*)(A.host.data() + D.fin_bias_off);
+    int32_t* fm = (int32_t*)(A.host.data() + D.fin_mul_off);
+    int32_t* fs = (int32_t*)(A.host.data() + D.fin_shift_off);
+    for (int r = 0; r < co; ++r) { fb[r] = L.bias[r]; fm[r] = L.M[r]; fs[r] = L.shift[r]; }
+    D.macs_per_pixel = (long long)co * live * 9;
+    D.bytes_per_pixel = (long long)live + (long long)co + 8LL * rows;  // + raw maps written and read once
+    D.wgt_bytes = D.macs_per_pixel;
+    D.wide = false;
+}
+
 size_t put_map(Arena& A, const std::vector<int>& rows, int n_pad) {
     const size_t off = A.alloc(4 * (size_t)n_pad);
     int32_t* m = (int32_t*)(A.host.data() + off);
@@ -309,6 +356,16 @@ void plan_net(Arena& A, const HostModel& m, const HostNet& N, DevNet& D, int buf
     D.layers.resize(nl);
     buf_w[BUF_XQ] = std::max(buf_w[BUF_XQ], D.cin_pad0);
     const int last_mode = N.kind == 0 ? MODE_COUPLE : MODE_CODES;
+    // the last layer: tap-expanded when it is 3x3 (every family here), else a plain GEMM
+    auto plan_last = [&](const HostLayer& H, const std::vector<int>& cols, int cin_pad, DevLayer& d) {
+        if (H.k == 3) {
+            pack_last_expanded(A, H, cols, cin_pad, last_mode, d);
+        } else {
+            pack_layer(A, H, kept_rows(H), cols, cin_pad, d);
+            d.mode = last_mode;
+            d.n_store = N.C_out;
+        }
+    };
     auto io = [](DevLayer& d, int ib, int ioff, int /*in width*/, int ob, int ooff, int /*out width*/, int mode) {
         d.in_buf = ib; d.in_off = ioff;
         d.out_buf = ob; d.out_off = ooff;
@@ -320,9 +377,8 @@ void plan_net(Arena& A, const HostModel& m, const HostNet& N, DevNet& D, int buf
         pack_layer(A, L[0], r0, identity_map(N.C_in), D.cin_pad0, D.layers[0]);
         io(D.layers[0], BUF_XQ, 0, D.cin_pad0, BUF_A, 0, fw, MODE_ACT);
         D.layers[0].n_store = fw;
-        pack_layer(A, L[1], kept_rows(L[1]), rank_map(L[0], 0), fw, D.layers[1]);
-        io(D.layers[1], BUF_A, 0, fw, -1, 0, 0, last_mode);
-        D.layers[1].n_store = N.C_out;
+        plan_last(L[1], rank_map(L[0], 0), fw, D.layers[1]);
+        D.layers[1].in_buf = BUF_A; D.layers[1].in_off = 0; D.layers[1].out_buf = -1; D.layers[1].out_off = 0;
         D.a_stride = fw;
         buf_w[BUF_A] = std::max(buf_w[BUF_A], fw);
     } else if (m.family == FAM_RESNET) {
@@ -359,9 +415,9 @@ void plan_net(Arena& A, const HostModel& m, const HostNet& N, DevNet& D, int buf
             io(D.layers[l + 1], BUF_B, 0, tw, BUF_A, 0, rw, MODE_ACT);
             stream_out(L[l + 1], D.layers[l + 1], r2);
         }
-        pack_layer(A, L[nl - 1], kept_rows(L[nl - 1]), identity_map(Wd), rw, D.layers[nl - 1]);
-        io(D.layers[nl - 1], BUF_A, 0, rw, -1, 0, 0, last_mode);
-        D.layers[nl - 1].n_store = N.C_out;
+        plan_last(L[nl - 1], identity_map(Wd), rw, D.layers[nl - 1]);
+        D.layers[nl - 1].in_buf = BUF_A; D.layers[nl - 1].in_off = 0; D.layers[nl - 1].out_buf = -1;
+        D.layers[nl - 1].out_off = 0;
     } else {
         // BUF_A: concatenation of the compacted feature blocks f0..f_depth; BUF_B: bottleneck g
         const int depth = (nl - 2) / 2;
@@ -392,9 +448,9 @@ void plan_net(Arena& A, const HostModel& m, const HostNet& N, DevNet& D, int buf
             io(D.layers[2 * l], BUF_B, 0, gw, BUF_A, blk_off[l], cw, MODE_ACT);
             D.layers[2 * l].n_store = blk_off[l + 1] - blk_off[l];
         }
-        pack_layer(A, L[nl - 1], kept_rows(L[nl - 1]), catpos, cw, D.layers[nl - 1]);
-        io(D.layers[nl - 1], BUF_A, 0, cw, -1, 0, 0, last_mode);
-        D.layers[nl - 1].n_store = N.C_out;
+        plan_last(L[nl - 1], catpos, cw, D.layers[nl - 1]);
+        D.layers[nl - 1].in_buf = BUF_A; D.layers[nl - 1].in_off = 0; D.layers[nl - 1].out_buf = -1;
+        D.layers[nl - 1].out_off = 0;
     }
 }
 
@@ -443,9 +499,9 @@ struct iodf_ctx {
 
 namespace {
 
-enum { CLS_QUANT_IN = 0, CLS_FILL_ZERO, CLS_INGEST, CLS_FACTOR_OUT, CLS_UNFACTOR, CLS_EMIT_X, NUM_FLOW_CLS };
+enum { CLS_QUANT_IN = 0, CLS_FILL_ZERO, CLS_INGEST, CLS_FACTOR_OUT, CLS_UNFACTOR, CLS_EMIT_X, CLS_TAPSUM, NUM_FLOW_CLS };
 const char* const kFlowClsName[NUM_FLOW_CLS] = {"k_quant_in", "k_fill_zero", "k_ingest_squeeze",
-                                                "k_factor_out", "k_unfactor", "k_emit_x"};
+                                                "k_factor_out", "k_unfactor", "k_emit_x", "conv_tapsum"};
 
 bool prof_start(iodf_ctx* ctx, hipStream_t st) {
     if (!ctx->prof_on || 2 * (ctx->prof_recs.size() + 1) > ctx->prof_ev.size()) return false;
@@ -464,6 +520,8 @@ void prof_stop(iodf_ctx* ctx, hipStream_t st, int cls, long long macs, long long
         HIP_TRY(call);                                      \
         if (p__) prof_stop(ctx, st, cls, macs, bytes);      \
     } while (0)
+
+static const int32_t* partial_of(const iodf_ctx* ctx);
 
 int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* codes, hipStream_t st) {
     const int lv = N.level;
@@ -508,17 +566,38 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
             a.state_c = N.C;
             a.idx_b = phi + N.C_in;
             a.sign = mode_sign;
-        } else {
+        } else if (L.mode == MODE_CODES) {
             a.codes = codes;
             a.codes_img_stride = ctx->d_codes;
             a.codes_off = ctx->code_off[lv];
+        } else if (!a.partial) {
+            return IODF_E_NOMEM;  // cannot happen: the scratch is sized for every raw layer at init
         }
-        const long long extra = L.mode == MODE_COUPLE ? 8LL * N.C_out : 0;  // state read + write
+        const int fmode = L.mode == MODE_RAW ? L.final_mode : L.mode;
+        const long long extra = fmode == MODE_COUPLE ? 8LL * N.C_out : 0;  // state read + write
         PROF_LAUNCH(ctx, st, conv_pick_tile(a), L.macs_per_pixel * npix,
                     (L.bytes_per_pixel + extra) * npix + L.wgt_bytes, launch_conv(a, st));
+        if (L.mode == MODE_RAW) {
+            TapSumArgs t;
+            memset(&t, 0, sizeof(t));
+            t.y = partial_of(ctx);
+            t.n_pad = L.n_pad; t.c_out = L.expand_c_out; t.h = h; t.w = w; t.npix = npix;
+            t.bias = (const int32_t*)(ctx->params + L.fin_bias_off);
+            t.mul = (const int32_t*)(ctx->params + L.fin_mul_off);
+            t.shift = (const int32_t*)(ctx->params + L.fin_shift_off);
+            t.mode = L.final_mode; t.relu = L.relu;
+            if (L.final_mode == MODE_COUPLE) {
+                t.state = ctx->state[lv]; t.state_c = N.C; t.idx_b = phi + N.C_in; t.sign = mode_sign;
+            } else {
+                t.codes = codes; t.codes_img_stride = ctx->d_codes; t.codes_off = ctx->code_off[lv];
+            }
+            PROF_LAUNCH(ctx, st, ntile + CLS_TAPSUM, 0, (36LL * L.expand_c_out + extra) * npix, launch_tapsum(t, st));
+        }
     }
     return IODF_OK;
 }
+
+static const int32_t* partial_of(const iodf_ctx* ctx) { return ctx->partial; }
 
 }  // namespace
 
