@@ -132,15 +132,23 @@ def main():
     roofline = None
     kernels = []
     if stats:
+        # a conv kernel's launches arrive split by filter size ("<kernel> 3x3" / "<kernel> 1x1"): list both,
+        # and take the roofline over the kernel as a whole (what rocprofv3 reports under one name)
+        per_kernel = {}
         for s in stats:
             avg_ms = s["total_ms"] / s["launches"]
             k = dict(name=s["name"], launches=s["launches"], total_ms=round(s["total_ms"], 3),
                      avg_ms=round(avg_ms, 5))
             if s["macs"]:
                 k["tops"] = round(2.0 * s["macs"] / (s["total_ms"] * 1e-3) / 1e12, 2)
+                k["frac_of_int8_peak"] = round(k["tops"] / INT8_PEAK_TOPS, 4)
             k["alg_gbs"] = round(s["bytes"] / (s["total_ms"] * 1e-3) / 1e9, 1)
             kernels.append(k)
-        dom = max((s for s in stats if s["macs"]), key=lambda s: s["total_ms"])
+            base = s["name"].rsplit(" ", 1)[0] if s["name"].endswith(("3x3", "1x1")) else s["name"]
+            agg = per_kernel.setdefault(base, dict(name=base, launches=0, total_ms=0.0, macs=0, bytes=0))
+            for f in ("launches", "total_ms", "macs", "bytes"):
+                agg[f] += s[f]
+        dom = max((s for s in per_kernel.values() if s["macs"]), key=lambda s: s["total_ms"])
         achieved = 2.0 * dom["macs"] / (dom["total_ms"] * 1e-3) / 1e12
         roofline = dict(bound="mfma", kernel=dom["name"], achieved=round(achieved, 2), peak=INT8_PEAK_TOPS,
                         unit="TOP/s", frac=round(achieved / INT8_PEAK_TOPS, 4),

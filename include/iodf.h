@@ -113,7 +113,8 @@ int iodf_inverse(iodf_ctx* ctx, const int32_t* z_dev, int batch, uint8_t* x_dev,
  * max_stats entries, one per kernel that ran) and *n_stats.
  */
 typedef struct iodf_kernel_stat {
-    char name[48];      /* kernel, e.g. "conv_igemm<256,256,2,2>" or "k_quant_in" */
+    char name[48];      /* kernel, e.g. "k_quant_in"; a conv kernel's launches are listed per filter size:
+                           "conv_igemm<256,256,2,4,4> 3x3" and "conv_igemm<256,256,2,4,4> 1x1" */
     int64_t launches;
     double total_ms;    /* sum of event-measured durations */
     int64_t macs;       /* algorithmic multiply-accumulates of those launches (kept channels, true widths) */

@@ -530,11 +530,11 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
     const int32_t* phi = (const int32_t*)(ctx->params + N.phi_off);
     const int ntile = conv_num_tiles();
     const long long plane = ctx->plane[lv];
-    PROF_LAUNCH(ctx, st, ntile + CLS_QUANT_IN, 0, (long long)npix * (4 * N.C_in + N.cin_pad0),
+    PROF_LAUNCH(ctx, st, CLS_QUANT_IN, 0, (long long)npix * (4 * N.C_in + N.cin_pad0),
                 launch_quant_in(ctx->state[lv], npix, h, w, N.C, phi, N.C_in, N.M_in, N.s_in, ctx->buf[lv][BUF_XQ],
                                 N.cin_pad0, plane, st));
     if (N.zero_a)  // whole planes of the residual stream; zeroing borders again is harmless
-        PROF_LAUNCH(ctx, st, ntile + CLS_FILL_ZERO, 0, (long long)npix * N.a_stride,
+        PROF_LAUNCH(ctx, st, CLS_FILL_ZERO, 0, (long long)npix * N.a_stride,
                     launch_fill_zero(ctx->buf[lv][BUF_A], (size_t)plane * (N.a_stride / 64), st));
     for (const DevLayer& L : N.layers) {
         ConvArgs a;
@@ -575,7 +575,7 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
         }
         const int fmode = L.mode == MODE_RAW ? L.final_mode : L.mode;
         const long long extra = fmode == MODE_COUPLE ? 8LL * N.C_out : 0;  // state read + write
-        PROF_LAUNCH(ctx, st, conv_pick_tile(a), L.macs_per_pixel * npix,
+        PROF_LAUNCH(ctx, st, NUM_FLOW_CLS + 2 * conv_pick_tile(a) + (a.taps == 9), L.macs_per_pixel * npix,
                     (L.bytes_per_pixel + extra) * npix + L.wgt_bytes, launch_conv(a, st));
         if (L.mode == MODE_RAW) {
             TapSumArgs t;
@@ -591,7 +591,7 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
             } else {
                 t.codes = codes; t.codes_img_stride = ctx->d_codes; t.codes_off = ctx->code_off[lv];
             }
-            PROF_LAUNCH(ctx, st, ntile + CLS_TAPSUM, 0, (36LL * L.expand_c_out + extra) * npix, launch_tapsum(t, st));
+            PROF_LAUNCH(ctx, st, CLS_TAPSUM, 0, (36LL * L.expand_c_out + extra) * npix, launch_tapsum(t, st));
         }
     }
     return IODF_OK;
@@ -803,7 +803,7 @@ static int enqueue_forward(iodf_ctx* ctx, const uint8_t* x_dev, int batch, int32
                            hipStream_t st) {
     const HostModel& m = ctx->shape;
     const int ntile = conv_num_tiles();
-    PROF_LAUNCH(ctx, st, ntile + CLS_INGEST, 0, 5LL * batch * ctx->d,
+    PROF_LAUNCH(ctx, st, CLS_INGEST, 0, 5LL * batch * ctx->d,
                 launch_ingest_squeeze(x_dev, batch, m.H, m.W, ctx->state[1], st));
     for (int lv = 1; lv <= m.levels; ++lv) {
         const int C = level_channels(lv), h = m.H >> lv, w = m.W >> lv;
@@ -814,7 +814,7 @@ static int enqueue_forward(iodf_ctx* ctx, const uint8_t* x_dev, int batch, int32
         }
         const int32_t* phi = (const int32_t*)(ctx->params + ctx->nets[n0 + m.couplings - 1].phi_off);
         const bool last = lv == m.levels;
-        PROF_LAUNCH(ctx, st, ntile + CLS_FACTOR_OUT, 0, 8LL * batch * C * h * w,
+        PROF_LAUNCH(ctx, st, CLS_FACTOR_OUT, 0, 8LL * batch * C * h * w,
                     launch_factor_out(ctx->state[lv], batch, h, w, C, phi, last ? 0 : C / 2, z_dev, ctx->d,
                                       ctx->z_off[lv], last ? nullptr : ctx->state[lv + 1], st));
         if (!last && m.has_heads && codes_dev) {
@@ -832,7 +832,7 @@ static int enqueue_inverse(iodf_ctx* ctx, const int32_t* z_dev, int batch, uint8
         const int n0 = ctx->first_net[lv];
         const int32_t* phi = (const int32_t*)(ctx->params + ctx->nets[n0 + m.couplings - 1].phi_off);
         const bool last = lv == m.levels;
-        PROF_LAUNCH(ctx, st, conv_num_tiles() + CLS_UNFACTOR, 0, 8LL * batch * C * h * w,
+        PROF_LAUNCH(ctx, st, CLS_UNFACTOR, 0, 8LL * batch * C * h * w,
                     launch_unfactor(ctx->state[lv], batch, h, w, C, phi, last ? 0 : C / 2, z_dev, ctx->d,
                                     ctx->z_off[lv], last ? nullptr : ctx->state[lv + 1], st));
         for (int k = m.couplings - 1; k >= 0; --k) {
@@ -840,7 +840,7 @@ static int enqueue_inverse(iodf_ctx* ctx, const int32_t* z_dev, int batch, uint8
             if (rc != IODF_OK) return rc;
         }
     }
-    PROF_LAUNCH(ctx, st, conv_num_tiles() + CLS_EMIT_X, 0, 5LL * batch * ctx->d,
+    PROF_LAUNCH(ctx, st, CLS_EMIT_X, 0, 5LL * batch * ctx->d,
                 launch_emit_x(ctx->state[1], batch, m.H, m.W, x_dev, ctx->range_errs, st));
     return IODF_OK;
 }
@@ -943,13 +943,16 @@ int iodf_profile_end(iodf_ctx* ctx, iodf_kernel_stat* stats, int max_stats, int*
     if (!ctx || !stats || !n_stats || max_stats < 1) return IODF_E_ARG;
     if (!ctx->prof_on) return IODF_E_ARG;
     ctx->prof_on = false;
-    const int ntile = conv_num_tiles();
-    const int ncls = ntile + NUM_FLOW_CLS;
+    // classes: the flow-state passes, then every conv tile split into its 1x1 and 3x3 launches
+    const int ncls = NUM_FLOW_CLS + 2 * conv_num_tiles();
     std::vector<iodf_kernel_stat> acc((size_t)ncls);
     for (int c = 0; c < ncls; ++c) {
         memset(&acc[c], 0, sizeof(iodf_kernel_stat));
-        const char* nm = c < ntile ? conv_tile_name(c) : kFlowClsName[c - ntile];
-        strncpy(acc[c].name, nm, sizeof(acc[c].name) - 1);
+        if (c < NUM_FLOW_CLS)
+            strncpy(acc[c].name, kFlowClsName[c], sizeof(acc[c].name) - 1);
+        else
+            snprintf(acc[c].name, sizeof(acc[c].name), "%s %s", conv_tile_name((c - NUM_FLOW_CLS) / 2),
+                     ((c - NUM_FLOW_CLS) & 1) ? "3x3" : "1x1");
     }
     int rc = IODF_OK;
     for (size_t i = 0; i < ctx->prof_recs.size(); ++i) {

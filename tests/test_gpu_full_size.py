@@ -2,7 +2,14 @@
 times. The oracle cannot run whole batches of the width-512 flows in reasonable
 time, so a few images of each batch are recomputed by the oracle one by one and
 compared bit-exactly; the rest of the batch is covered by properties that hold at
-any size: exact round trip and per-image batch invariance."""
+any size: exact round trip, and every image's result being the same when the batch
+is cut into ragged chunks (other tile positions, other tile tails) or run alone.
+
+IODF_FULL_PARITY=1 in the environment makes the oracle recompute EVERY image of each
+batch instead of the sample (cfg4: about ten minutes of host time).
+IODF_FULL_PARITY_ONLY=cfg4 restricts that to one configuration."""
+import os
+
 import numpy as np
 import pytest
 
@@ -12,8 +19,11 @@ from util import gpu_flow, images, oracle_model, to_gpu
 pytestmark = pytest.mark.gpu
 
 
-def _sampled(capsys, name, batch, sample, invariance=()):
+def _sampled(capsys, name, batch, sample, invariance=(), chunk=None):
     import torch
+    full = os.environ.get("IODF_FULL_PARITY") == "1" and os.environ.get("IODF_FULL_PARITY_ONLY", name) == name
+    if full:
+        sample = tuple(range(batch))
 
     def say(*a):
         with capsys.disabled():   # progress lines must reach the terminal while the test runs
@@ -33,6 +43,15 @@ def _sampled(capsys, name, batch, sample, invariance=()):
     for i in invariance:
         zi, ci = flow.forward(xg[i:i + 1].contiguous())
         assert torch.equal(zi[0], z[i]) and torch.equal(ci[0], codes[i]), "batch invariance"
+    if chunk:
+        # the whole batch again in ragged chunks: every image lands in other tiles
+        for lo in range(0, batch, chunk):
+            hi = min(batch, lo + chunk)
+            zi, ci = flow.forward(xg[lo:hi].contiguous())
+            assert torch.equal(zi, z[lo:hi]) and torch.equal(ci, codes[lo:hi]), "chunk %d..%d" % (lo, hi)
+            xi = flow.inverse(zi)
+            assert torch.equal(xi, xg[lo:hi]), "chunked round trip %d..%d" % (lo, hi)
+        say("ragged chunks of", chunk, "match")
     zc, cc = z.cpu().numpy(), codes.cpu().numpy()
     flow.close()
     om = oracle_model(name)
@@ -45,12 +64,12 @@ def _sampled(capsys, name, batch, sample, invariance=()):
 
 @pytest.mark.timeout(600)
 def test_cfg3_sampled(capsys):
-    _sampled(capsys, "cfg3", CONFIGS["cfg3"].batch, sample=(131, 255), invariance=(7,))
+    _sampled(capsys, "cfg3", CONFIGS["cfg3"].batch, sample=(0, 64, 131, 200, 255), invariance=(7,), chunk=53)
 
 
 @pytest.mark.timeout(900)
 def test_cfg4_sampled(capsys):
-    _sampled(capsys, "cfg4", CONFIGS["cfg4"].batch, sample=(77,), invariance=(64,))
+    _sampled(capsys, "cfg4", CONFIGS["cfg4"].batch, sample=(0, 77, 127), invariance=(64,), chunk=37)
 
 
 @pytest.mark.timeout(900)
@@ -61,5 +80,5 @@ def test_cfg5_batch1(capsys):
 
 @pytest.mark.timeout(900)
 def test_cfg5_batch1024_sampled(capsys):
-    # throughput shape; oracle on one sampled image, batch invariance on others
-    _sampled(capsys, "cfg5", 1024, sample=(1023,), invariance=(1, 511))
+    # throughput shape; oracle on sampled images, batch invariance on the others
+    _sampled(capsys, "cfg5", 1024, sample=(0, 300, 777, 1023), invariance=(1, 511), chunk=301)
