@@ -24,8 +24,9 @@ def lib():
     global _LIB
     if _LIB is None:
         path = os.path.join(_HERE, "liboracle.so")
-        src = os.path.join(_HERE, "iodf_oracle.c")
-        if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(src):
+        srcs = [os.path.join(_HERE, f) for f in ("iodf_oracle.c", "iodf_oracle.h", "iodf_codec_oracle.c",
+                                                 "iodf_codec_oracle.h")]
+        if not os.path.exists(path) or os.path.getmtime(path) < max(os.path.getmtime(f) for f in srcs):
             build()
         L = ctypes.CDLL(path)
         vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
@@ -61,6 +62,31 @@ def lib():
         L.orc_inverse.restype = ci
         L.orc_inverse.argtypes = [vp, vp, ci, vp, ctypes.POINTER(i64)]
         L.orc_last_max_abs_state.restype = i64
+        u32, u64 = ctypes.c_uint32, ctypes.c_uint64
+        L.orc_prior_tables.restype = None
+        L.orc_prior_tables.argtypes = [vp, vp]
+        L.orc_prior_sigmoid.restype = i64
+        L.orc_prior_sigmoid.argtypes = [i64]
+        L.orc_prior_cdf.restype = i64
+        L.orc_prior_cdf.argtypes = [ci, ci]
+        L.orc_prior_cf.restype = i64
+        L.orc_prior_cf.argtypes = [vp, vp, vp, i64, vp, vp]
+        L.orc_rans_push.restype = u64
+        L.orc_rans_push.argtypes = [u64, u32, u32, ctypes.POINTER(ci), ctypes.POINTER(u32)]
+        L.orc_rans_pop.restype = u64
+        L.orc_rans_pop.argtypes = [u64, u32, u32]
+        L.orc_codec_header_words.restype = i64
+        L.orc_codec_header_words.argtypes = [ci]
+        L.orc_codec_encode_image.restype = i64
+        L.orc_codec_encode_image.argtypes = [vp, vp, ci, vp, vp, vp, vp, i64, ctypes.POINTER(i64)]
+        L.orc_codec_decode_chunk.restype = ci
+        L.orc_codec_decode_chunk.argtypes = [vp, i64, ci, vp, ci, vp, vp, vp]
+        L.orc_codec_max_words.restype = i64
+        L.orc_codec_max_words.argtypes = [vp]
+        L.orc_encode.restype = ci
+        L.orc_encode.argtypes = [vp, vp, ci, vp, i64, vp, ctypes.POINTER(i64)]
+        L.orc_decode.restype = ci
+        L.orc_decode.argtypes = [vp, vp, i64, ci, vp, ctypes.POINTER(i64)]
         _LIB = L
     return _LIB
 
@@ -182,6 +208,99 @@ class Model:
             raise RuntimeError("oracle inverse failed (%d)" % rc)
         return x, int(errs.value)
 
+    def codec_max_words(self):
+        return int(lib().orc_codec_max_words(self._h))
+
+    def encode(self, x, cap=None):
+        """x u8 [B,3,H,W] -> (containers uint32 [B,cap], sizes uint32 [B], clamped count)."""
+        x = np.ascontiguousarray(x, dtype=np.uint8)
+        cap = int(cap or self.codec_max_words())
+        out = np.zeros((x.shape[0], cap), np.uint32)
+        sizes = np.zeros(x.shape[0], np.uint32)
+        cl = ctypes.c_int64(0)
+        rc = lib().orc_encode(self._h, _p(x), x.shape[0], _p(out), cap, _p(sizes), ctypes.byref(cl))
+        if rc:
+            raise RuntimeError("orc_encode failed: %d" % rc)
+        return out, sizes, int(cl.value)
+
+    def decode(self, cont, shape):
+        """containers uint32 [B,cap] -> (x u8 [B,*shape], error count)."""
+        cont = np.ascontiguousarray(cont, dtype=np.uint32)
+        x = np.zeros((cont.shape[0],) + tuple(shape), np.uint8)
+        errs = ctypes.c_int64(0)
+        rc = lib().orc_decode(self._h, _p(cont), cont.shape[1], cont.shape[0], _p(x), ctypes.byref(errs))
+        if rc:
+            raise RuntimeError("orc_decode failed: %d" % rc)
+        return x, int(errs.value)
+
     @staticmethod
     def last_max_abs_state():
         return int(lib().orc_last_max_abs_state())
+
+
+# ---- entropy-coding side (iodf_codec_oracle.h) ----
+MASS_BITS, ALPHA_R, SIG_BITS, LANES = 24, 8192, 30, 16
+
+
+def prior_tables():
+    sig = np.empty(3073, np.int32)
+    inv = np.empty(256, np.int64)
+    lib().orc_prior_tables(_p(sig), _p(inv))
+    return sig, inv
+
+
+def prior_sigmoid(T):
+    return int(lib().orc_prior_sigmoid(int(T)))
+
+
+def prior_cdf(r, l):
+    return int(lib().orc_prior_cdf(int(r), int(l)))
+
+
+def prior_cf(z, m=None, l=None):
+    """Masses (C, F) of latents z with mean codes m and log-scale codes l (None: defaults)."""
+    z = np.ascontiguousarray(z, np.int32).ravel()
+    m = None if m is None else np.ascontiguousarray(m, np.int8).ravel()
+    l = None if l is None else np.ascontiguousarray(l, np.int8).ravel()
+    C = np.empty(z.size, np.int32)
+    F = np.empty(z.size, np.int32)
+    clamped = lib().orc_prior_cf(_p(z), _p(m), _p(l), z.size, _p(C), _p(F))
+    return C, F, int(clamped)
+
+
+def rans_push(X, C, F):
+    """One encoder update; returns (new state, shed word or None)."""
+    e, w = ctypes.c_int(0), ctypes.c_uint32(0)
+    X2 = lib().orc_rans_push(int(X), int(C), int(F), ctypes.byref(e), ctypes.byref(w))
+    return int(X2), (int(w.value) if e.value else None)
+
+
+def rans_pop(X, C, F):
+    return int(lib().orc_rans_pop(int(X), int(C), int(F)))
+
+
+def codec_header_words(n_chunks):
+    return int(lib().orc_codec_header_words(int(n_chunks)))
+
+
+def codec_encode_image(z, codes, n, z_off, code_off, cap):
+    z = np.ascontiguousarray(z, np.int32)
+    codes = None if codes is None else np.ascontiguousarray(codes, np.int8)
+    n = np.ascontiguousarray(n, np.int64)
+    z_off = np.ascontiguousarray(z_off, np.int64)
+    code_off = np.ascontiguousarray(code_off, np.int64)
+    out = np.zeros(int(cap), np.uint32)
+    cl = ctypes.c_int64(0)
+    w = lib().orc_codec_encode_image(_p(z), _p(codes), n.size, _p(n), _p(z_off), _p(code_off), _p(out), int(cap),
+                                     ctypes.byref(cl))
+    return out, int(w), int(cl.value)
+
+
+def codec_decode_chunk(cont, n, c, m=None, l=None):
+    cont = np.ascontiguousarray(cont, np.uint32)
+    n = np.ascontiguousarray(n, np.int64)
+    m = None if m is None else np.ascontiguousarray(m, np.int8)
+    l = None if l is None else np.ascontiguousarray(l, np.int8)
+    zc = np.zeros(int(n[c]), np.int32)
+    rc = lib().orc_codec_decode_chunk(_p(cont), cont.size, n.size, _p(n), int(c), _p(m), _p(l), _p(zc))
+    return zc, int(rc)

@@ -4,6 +4,7 @@
  * gate masks, one rounding rule. Nothing here is shared with the GPU library.
  */
 #include "iodf_oracle.h"
+#include "iodf_codec_oracle.h"
 
 #include <omp.h>
 #include <stdlib.h>
@@ -410,6 +411,108 @@ int orc_inverse(const orc_model* m, const int32_t* z, int batch, uint8_t* x, int
         }
     }
     if (range_errors) *range_errors = errs;
+    free(cur); free(tmp); free(t);
+    return rc;
+}
+
+/* ---- compressor: flow + prior + coder (Sec. 3, Sec. 5.2, App. A) ---- */
+
+/* Chunk c = level c + 1: latent count, offset in z, offset in codes (-1: no head). */
+static int chunk_tables(const orc_model* m, int64_t* n, int64_t* z_off, int64_t* code_off) {
+    int64_t zo = 0, co = 0;
+    for (int lv = 1; lv <= m->levels; ++lv) {
+        const int C = level_channels(lv);
+        const int64_t hw = (int64_t)(m->H >> lv) * (m->W >> lv);
+        const int64_t cz = lv < m->levels ? C - C / 2 : C;
+        n[lv - 1] = cz * hw;
+        z_off[lv - 1] = zo;
+        zo += cz * hw;
+        if (m->has_heads && lv < m->levels) { code_off[lv - 1] = co; co += 2 * cz * hw; }
+        else code_off[lv - 1] = -1;
+    }
+    return m->levels;
+}
+
+int64_t orc_codec_max_words(const orc_model* m) {
+    return orc_codec_header_words(m->levels) + orc_model_d(m);
+}
+
+int orc_encode(const orc_model* m, const uint8_t* x, int batch, uint32_t* out, int64_t cap, uint32_t* sizes,
+               int64_t* n_clamped) {
+    const int64_t d = orc_model_d(m), dc = orc_model_d_codes(m);
+    int64_t n[16], z_off[16], code_off[16], clamped = 0;
+    const int nch = chunk_tables(m, n, z_off, code_off);
+    int32_t* z = (int32_t*)malloc((size_t)d * sizeof(int32_t));
+    int8_t* codes = (int8_t*)malloc((size_t)(dc > 0 ? dc : 1));
+    int rc = 0;
+    for (int b = 0; b < batch && !rc; ++b) {
+        rc = orc_forward(m, x + (size_t)b * d, 1, z, codes);
+        if (rc) break;
+        int64_t cl = 0;
+        const int64_t w = orc_codec_encode_image(z, codes, nch, n, z_off, code_off, out + (size_t)b * cap, cap, &cl);
+        sizes[b] = (uint32_t)w;
+        clamped += cl;
+    }
+    if (n_clamped) *n_clamped = clamped;
+    free(z); free(codes);
+    return rc;
+}
+
+/* Decoding interleaves the coder with the flow: the latents of level lv can only be
+ * read once the deeper levels have been inverted, because their prior parameters come
+ * from the head on the half that continued downwards. */
+int orc_decode(const orc_model* m, const uint32_t* cont, int64_t cap, int batch, uint8_t* x, int64_t* errors) {
+    const int64_t d = orc_model_d(m);
+    int64_t n[16], z_off[16], code_off[16], errs = 0;
+    const int nch = chunk_tables(m, n, z_off, code_off);
+    int first_net[16];
+    {
+        int net = 0;
+        for (int lv = 1; lv <= m->levels; ++lv) {
+            first_net[lv] = net;
+            net += m->couplings + ((m->has_heads && lv < m->levels) ? 1 : 0);
+        }
+    }
+    int32_t* cur = (int32_t*)malloc((size_t)d * sizeof(int32_t));
+    int32_t* tmp = (int32_t*)malloc((size_t)d * sizeof(int32_t));
+    int8_t* t = (int8_t*)malloc((size_t)d * 2);
+    int rc = 0;
+    for (int b = 0; b < batch && !rc; ++b) {
+        const uint32_t* cb = cont + (size_t)b * cap;
+        for (int lv = m->levels; lv >= 1 && !rc; --lv) {
+            const int C = level_channels(lv), H = m->H >> lv, W = m->W >> lv, hw = H * W;
+            const int Ck = lv == m->levels ? 0 : C / 2;
+            const int8_t *mc = NULL, *lc = NULL;
+            if (code_off[lv - 1] >= 0) {
+                /* head on the kept half (already in cur[0 .. Ck*hw)) */
+                rc = orc_net_eval(m, first_net[lv] + m->couplings, cur, H, W, t);
+                if (rc) break;
+                mc = t;
+                lc = t + n[lv - 1];
+            }
+            if (orc_codec_decode_chunk(cb, cap, nch, n, lv - 1, mc, lc, cur + (size_t)Ck * hw) != 0) ++errs;
+            for (int k = m->couplings - 1; k >= 0 && !rc; --k) {
+                const int net = first_net[lv] + k;
+                const orc_net* N = &m->nets[net];
+                const int Ca = C / 2;
+                rc = orc_net_eval(m, net, cur, H, W, t);
+                for (int i = 0; i < (C - Ca) * hw; ++i) cur[(size_t)Ca * hw + i] -= t[i];
+                for (int c = 0; c < C; ++c)
+                    memcpy(tmp + (size_t)N->perm[c] * hw, cur + (size_t)c * hw, (size_t)hw * sizeof(int32_t));
+                memcpy(cur, tmp, (size_t)C * hw * sizeof(int32_t));
+            }
+            orc_unsqueeze(cur, C / 4, 2 * H, 2 * W, tmp);
+            memcpy(cur, tmp, (size_t)C * hw * sizeof(int32_t));
+        }
+        uint8_t* xb = x + (size_t)b * d;
+        for (int64_t i = 0; i < d; ++i) {
+            int32_t v = cur[i] + 128;
+            if (v < 0) { v = 0; ++errs; }
+            if (v > 255) { v = 255; ++errs; }
+            xb[i] = (uint8_t)v;
+        }
+    }
+    if (errors) *errors = errs;
     free(cur); free(tmp); free(t);
     return rc;
 }

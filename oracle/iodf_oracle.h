@@ -74,6 +74,16 @@ int orc_inverse(const orc_model* m, const int32_t* z, int batch, uint8_t* x, int
 /* Largest |flow state| seen by the last orc_forward call (for the state bound). */
 int64_t orc_last_max_abs_state(void);
 
+/* Compressor built on the flow (Sec. 3, Sec. 5.2, App. A; coder and prior in
+ * iodf_codec_oracle.h): x -> one container of 32-bit words per image, written at
+ * out + b * cap (at most cap words each); sizes[b] = words the container needs.
+ * *n_clamped counts latents whose residual fell outside the prior's alphabet. */
+int64_t orc_codec_max_words(const orc_model* m);
+int orc_encode(const orc_model* m, const uint8_t* x, int batch, uint32_t* out, int64_t cap, uint32_t* sizes,
+               int64_t* n_clamped);
+/* Containers -> x. *errors counts malformed lanes and pixels outside [0,255]. */
+int orc_decode(const orc_model* m, const uint32_t* cont, int64_t cap, int batch, uint8_t* x, int64_t* errors);
+
 #ifdef __cplusplus
 }
 #endif
