@@ -58,7 +58,14 @@ enum {
     IODF_Q_IMAGE_H = 7,
     IODF_Q_IMAGE_W = 8,
     IODF_Q_CONV_LAUNCHES = 9,    /* convolution kernels per forward call */
-    IODF_Q_WIDE_MACS_FORWARD = 10 /* of IODF_Q_MACS_FORWARD, the part in layers whose C_in and C_out are both >= 128 */
+    IODF_Q_WIDE_MACS_FORWARD = 10, /* of IODF_Q_MACS_FORWARD, the part in layers whose C_in and C_out are both >= 128 */
+    IODF_Q_CODEC_HEADER_WORDS = 11, /* 32-bit words of a container's header: 1 + 3 * 16 * levels */
+    IODF_Q_CODEC_MAX_WORDS = 12,    /* capacity no container exceeds: header + d (a latent sheds at most one word) */
+    IODF_Q_CODEC_CLAMPED = 13,      /* latents whose residual z - mu left [-8192, 8191] and was clamped (the image
+                                       then does NOT decode back); 13..15 synchronise and reset like RANGE_ERRORS */
+    IODF_Q_CODEC_OVERFLOWS = 14,    /* containers that needed more than cap_words (truncated, unusable) */
+    IODF_Q_CODEC_BROKEN_LANES = 15  /* coder lanes that iodf_decode could not read back to their initial state
+                                       (malformed or foreign container) */
 };
 
 /*
@@ -103,6 +110,38 @@ int iodf_forward(iodf_ctx* ctx, const uint8_t* x_dev, int batch, int32_t* z_dev,
  *          value outside [0,255]: the byte is saturated and counted (IODF_Q_RANGE_ERRORS).
  */
 int iodf_inverse(iodf_ctx* ctx, const int32_t* z_dev, int batch, uint8_t* x_dev, void* stream);
+
+/*
+ * Compressor: bits = rANS(f(x); p_Z) and back (Sec. 3 prior, Sec. 5.2 "actual encoding", App. A).
+ *
+ * Prior of a latent z with mean code m and log-scale code l (int8, from the level's head;
+ * m = 0, l = 96 for latents without a head): discretised logistic with mu = 2 m, s = 2^(l/16),
+ * evaluated in integers: cumulative mass G(r) = (r + 8192) + floor((2^24 - 16384) *
+ * S((2r - 1)/(2s)) / 2^30) over the residual r = z - mu in [-8192, 8191], S a 3073-entry table
+ * of round(2^30 sigma(t)) at t = -24 + j/64 with linear interpolation; C = G(r), F = G(r+1) - G(r)
+ * >= 1, total mass M = 2^24.
+ * Coder: App. A's recurrences on a 64-bit state in [2^31, 2^63) that starts at 2^31 and sheds /
+ * refills 32-bit words; a level's latents are dealt round-robin to 16 independent lanes.
+ * Container of one image (little-endian u32 words): total word count; words per (level, lane);
+ * final state (low, high) per (level, lane); then each lane's words in decoding order.
+ *
+ * iodf_prior_cf: z_dev int32 [batch][d], codes_dev int8 [batch][code bytes] (ignored without
+ *   heads) -> c_dev, f_dev int32 [batch][d] (device).
+ * iodf_encode: x_dev uint8 [batch][3][H][W] -> words_dev u32 [batch][cap_words] (one container
+ *   per image, never written past cap_words) and sizes_dev u32 [batch] (words each container
+ *   needs; larger than cap_words means truncated, see IODF_Q_CODEC_OVERFLOWS).
+ * iodf_decode: containers -> x_dev. cap_words must be at least the header size. Malformed
+ *   containers never cause out-of-range reads; they are counted (IODF_Q_CODEC_BROKEN_LANES).
+ * The first of these calls on a context allocates the compressor's device buffers. Calls on one
+ * context must not overlap. iodf_codec_tables copies the two tables (host: int32 sig[3073],
+ * int64 inv[256] = round(2^23 * 2^(-l/16)) at index l + 128); it needs no GPU.
+ */
+int iodf_prior_cf(iodf_ctx* ctx, const int32_t* z_dev, const int8_t* codes_dev, int batch, int32_t* c_dev,
+                  int32_t* f_dev, void* stream);
+int iodf_encode(iodf_ctx* ctx, const uint8_t* x_dev, int batch, uint32_t* words_dev, int64_t cap_words,
+                uint32_t* sizes_dev, void* stream);
+int iodf_decode(iodf_ctx* ctx, const uint32_t* words_dev, int64_t cap_words, int batch, uint8_t* x_dev, void* stream);
+int iodf_codec_tables(int32_t* sig_host, int64_t* inv_host);
 
 /*
  * Per-kernel timing for roofline reports (the paper reports latency only, Sec. 5.2; this is

@@ -18,10 +18,12 @@ _LIB = None
 
 IODF_Q_Z_ELEMS, IODF_Q_CODE_BYTES, IODF_Q_WORKSPACE_BYTES, IODF_Q_MACS_FORWARD, IODF_Q_MACS_INVERSE, \
     IODF_Q_RANGE_ERRORS, IODF_Q_MAX_BATCH, IODF_Q_IMAGE_H, IODF_Q_IMAGE_W, IODF_Q_CONV_LAUNCHES, \
-    IODF_Q_WIDE_MACS_FORWARD = range(11)
+    IODF_Q_WIDE_MACS_FORWARD, IODF_Q_CODEC_HEADER_WORDS, IODF_Q_CODEC_MAX_WORDS, IODF_Q_CODEC_CLAMPED, \
+    IODF_Q_CODEC_OVERFLOWS, IODF_Q_CODEC_BROKEN_LANES = range(16)
 
 EXPORTS = ["iodf_init", "iodf_forward", "iodf_inverse", "iodf_query", "iodf_free", "iodf_strerror",
-           "iodf_last_hip_error", "iodf_profile_begin", "iodf_profile_end"]
+           "iodf_last_hip_error", "iodf_profile_begin", "iodf_profile_end", "iodf_prior_cf", "iodf_encode",
+           "iodf_decode", "iodf_codec_tables"]
 
 
 class KernelStat(ctypes.Structure):
@@ -79,6 +81,14 @@ def load_library(build_if_missing=True):
     L.iodf_profile_begin.argtypes = [vp, ci]
     L.iodf_profile_end.restype = ci
     L.iodf_profile_end.argtypes = [vp, ctypes.POINTER(KernelStat), ci, ctypes.POINTER(ci)]
+    L.iodf_prior_cf.restype = ci
+    L.iodf_prior_cf.argtypes = [vp, vp, vp, ci, vp, vp, vp]
+    L.iodf_encode.restype = ci
+    L.iodf_encode.argtypes = [vp, vp, ci, vp, ctypes.c_int64, vp, vp]
+    L.iodf_decode.restype = ci
+    L.iodf_decode.argtypes = [vp, vp, ctypes.c_int64, ci, vp, vp]
+    L.iodf_codec_tables.restype = ci
+    L.iodf_codec_tables.argtypes = [vp, vp]
     _LIB = L
     return L
 
@@ -108,6 +118,26 @@ def iodf_forward(ctx, x_ptr, batch, z_ptr, codes_ptr, stream):
 
 def iodf_inverse(ctx, z_ptr, batch, x_ptr, stream):
     _check(load_library().iodf_inverse(ctx, z_ptr, int(batch), x_ptr, stream))
+
+
+def iodf_prior_cf(ctx, z_ptr, codes_ptr, batch, c_ptr, f_ptr, stream):
+    _check(load_library().iodf_prior_cf(ctx, z_ptr, codes_ptr, int(batch), c_ptr, f_ptr, stream))
+
+
+def iodf_encode(ctx, x_ptr, batch, words_ptr, cap_words, sizes_ptr, stream):
+    _check(load_library().iodf_encode(ctx, x_ptr, int(batch), words_ptr, int(cap_words), sizes_ptr, stream))
+
+
+def iodf_decode(ctx, words_ptr, cap_words, batch, x_ptr, stream):
+    _check(load_library().iodf_decode(ctx, words_ptr, int(cap_words), int(batch), x_ptr, stream))
+
+
+def iodf_codec_tables():
+    """(sig int32 [3073], inv int64 [256]) as the library builds them; needs no GPU."""
+    sig = np.empty(3073, np.int32)
+    inv = np.empty(256, np.int64)
+    _check(load_library().iodf_codec_tables(sig.ctypes.data_as(ctypes.c_void_p), inv.ctypes.data_as(ctypes.c_void_p)))
+    return sig, inv
 
 
 def iodf_query(ctx, what):
@@ -177,6 +207,49 @@ class Flow:
         iodf_inverse(self._ctx, ctypes.c_void_p(z.data_ptr()) if b else None, b,
                      ctypes.c_void_p(x.data_ptr()) if b else None, self._stream())
         return x
+
+    def prior_cf(self, z, codes=None):
+        """Masses (C, F) of every latent under the prior the codes describe."""
+        torch = self._torch
+        assert z.is_cuda and z.dtype == torch.int32 and z.is_contiguous()
+        b = z.shape[0]
+        C = torch.empty((b, self.d), dtype=torch.int32, device=self.device)
+        F = torch.empty((b, self.d), dtype=torch.int32, device=self.device)
+        cp = ctypes.c_void_p(codes.data_ptr()) if (codes is not None and self.d_codes and b) else None
+        iodf_prior_cf(self._ctx, ctypes.c_void_p(z.data_ptr()) if b else None, cp, b,
+                      ctypes.c_void_p(C.data_ptr()) if b else None, ctypes.c_void_p(F.data_ptr()) if b else None,
+                      self._stream())
+        return C, F
+
+    def encode(self, x, cap_words=None, words=None, sizes=None):
+        """x u8 [B,3,H,W] -> (containers int32-viewed-as-u32 [B,cap_words], sizes [B] in words)."""
+        torch = self._torch
+        assert x.is_cuda and x.dtype == torch.uint8 and x.is_contiguous()
+        b = x.shape[0]
+        cap = int(cap_words or self.query(IODF_Q_CODEC_MAX_WORDS))
+        if words is None:
+            words = torch.zeros((b, cap), dtype=torch.int32, device=self.device)
+        if sizes is None:
+            sizes = torch.zeros((b,), dtype=torch.int32, device=self.device)
+        iodf_encode(self._ctx, ctypes.c_void_p(x.data_ptr()) if b else None, b,
+                    ctypes.c_void_p(words.data_ptr()) if b else None, cap,
+                    ctypes.c_void_p(sizes.data_ptr()) if b else None, self._stream())
+        return words, sizes
+
+    def decode(self, words, x=None):
+        torch = self._torch
+        assert words.is_cuda and words.dtype == torch.int32 and words.is_contiguous() and words.dim() == 2
+        b, cap = words.shape
+        if x is None:
+            x = torch.empty((b, 3, self.H, self.W), dtype=torch.uint8, device=self.device)
+        iodf_decode(self._ctx, ctypes.c_void_p(words.data_ptr()) if b else None, cap, b,
+                    ctypes.c_void_p(x.data_ptr()) if b else None, self._stream())
+        return x
+
+    def codec_errors(self):
+        """(clamped residuals, overflowing containers, broken lanes) since the last call; synchronises."""
+        return tuple(iodf_query(self._ctx, q) for q in (IODF_Q_CODEC_CLAMPED, IODF_Q_CODEC_OVERFLOWS,
+                                                        IODF_Q_CODEC_BROKEN_LANES))
 
     def profile_begin(self, max_launches):
         iodf_profile_begin(self._ctx, max_launches)

@@ -13,6 +13,7 @@
 #include <string>
 #include <vector>
 
+#include "codec_kernels.h"
 #include "conv.h"
 #include "flow_kernels.h"
 
@@ -490,6 +491,17 @@ struct iodf_ctx {
     uint8_t* stage_x = nullptr;
     int32_t* stage_z = nullptr;
     int8_t* stage_codes = nullptr;
+    // Compressor (iodf_encode / iodf_decode / iodf_prior_cf): allocated by the first call that needs it
+    bool codec_ready = false;
+    ChunkTable chunks;                 // chunk c = level c + 1
+    long long lane_words_per_image = 0;
+    int32_t* codec_sig = nullptr;      // tables of the integer prior
+    int64_t* codec_inv = nullptr;
+    int32_t* codec_z = nullptr;        // [max_batch][d]
+    int8_t* codec_codes = nullptr;     // [max_batch][d_codes]
+    uint32_t* lane_words = nullptr;    // [max_batch][lane_words_per_image]
+    uint32_t* lane_meta = nullptr;     // [max_batch][n_chunks * 16][4]
+    unsigned long long* codec_errs = nullptr;  // [3]: clamped residuals, overflowing containers, broken lanes
     // optional per-launch timing (iodf_profile_begin / iodf_profile_end)
     struct ProfRec { int cls; long long macs, bytes; };
     bool prof_on = false;
@@ -499,9 +511,11 @@ struct iodf_ctx {
 
 namespace {
 
-enum { CLS_QUANT_IN = 0, CLS_FILL_ZERO, CLS_INGEST, CLS_FACTOR_OUT, CLS_UNFACTOR, CLS_EMIT_X, CLS_TAPSUM, NUM_FLOW_CLS };
+enum { CLS_QUANT_IN = 0, CLS_FILL_ZERO, CLS_INGEST, CLS_FACTOR_OUT, CLS_UNFACTOR, CLS_EMIT_X, CLS_TAPSUM,
+       CLS_PRIOR_CF, CLS_RANS_ENCODE, CLS_RANS_PACK, CLS_RANS_DECODE, NUM_FLOW_CLS };
 const char* const kFlowClsName[NUM_FLOW_CLS] = {"k_quant_in", "k_fill_zero", "k_ingest_squeeze",
-                                                "k_factor_out", "k_unfactor", "k_emit_x", "conv_tapsum"};
+                                                "k_factor_out", "k_unfactor", "k_emit_x", "conv_tapsum",
+                                                "k_prior_cf", "k_rans_encode", "k_rans_pack", "k_rans_decode_chunk"};
 
 bool prof_start(iodf_ctx* ctx, hipStream_t st) {
     if (!ctx->prof_on || 2 * (ctx->prof_recs.size() + 1) > ctx->prof_ev.size()) return false;
@@ -788,6 +802,9 @@ void iodf_free(iodf_ctx* ctx) {
     for (int32_t* s : ctx->state)
         if (s) (void)hipFree(s);
     if (ctx->range_errs) (void)hipFree(ctx->range_errs);
+    for (void* q : {(void*)ctx->codec_sig, (void*)ctx->codec_inv, (void*)ctx->codec_z, (void*)ctx->codec_codes,
+                    (void*)ctx->lane_words, (void*)ctx->lane_meta, (void*)ctx->codec_errs})
+        if (q) (void)hipFree(q);
     for (auto& g : ctx->graphs) (void)hipGraphExecDestroy(g.exec);
     if (ctx->cap_stream) (void)hipStreamDestroy(ctx->cap_stream);
     if (ctx->stage_x) (void)hipFree(ctx->stage_x);
@@ -918,6 +935,150 @@ int iodf_inverse(iodf_ctx* ctx, const int32_t* z_dev, int batch, uint8_t* x_dev,
     return IODF_OK;
 }
 
+// ---- compressor: flow + prior + coder ----
+
+// Device buffers and tables of the compressor, on first use.
+static int codec_prepare(iodf_ctx* ctx) {
+    if (ctx->codec_ready) return IODF_OK;
+    const HostModel& m = ctx->shape;
+    if (m.levels > kMaxChunks) return IODF_E_ARG;
+    ChunkTable& ct = ctx->chunks;
+    memset(&ct, 0, sizeof(ct));
+    ct.n_chunks = m.levels;
+    long long lane_off = 0;
+    for (int lv = 1; lv <= m.levels; ++lv) {
+        const int C = level_channels(lv);
+        const long long hw = (long long)(m.H >> lv) * (m.W >> lv);
+        const long long n = (lv < m.levels ? C - C / 2 : C) * hw;
+        ct.n[lv - 1] = (int)n;
+        ct.z_off[lv - 1] = ctx->z_off[lv];
+        ct.code_off[lv - 1] = (m.has_heads && lv < m.levels) ? ctx->code_off[lv] : -1;
+        ct.lane_cap[lv - 1] = (int)((n + kLanes - 1) / kLanes) + 1;
+        ct.lane_off[lv - 1] = lane_off;
+        lane_off += (long long)kLanes * ct.lane_cap[lv - 1];
+    }
+    ctx->lane_words_per_image = lane_off;
+    std::vector<int32_t> sig(kSigEntries);
+    std::vector<int64_t> inv(256);
+    codec_make_tables(sig.data(), inv.data());
+    const size_t B = (size_t)ctx->max_batch;
+    struct { void** p; size_t bytes; } want[] = {
+        {(void**)&ctx->codec_sig, sizeof(int32_t) * kSigEntries},
+        {(void**)&ctx->codec_inv, sizeof(int64_t) * 256},
+        {(void**)&ctx->codec_z, 4 * B * (size_t)ctx->d},
+        {(void**)&ctx->codec_codes, B * (size_t)std::max<long long>(ctx->d_codes, 1)},
+        {(void**)&ctx->lane_words, 4 * B * (size_t)lane_off},
+        {(void**)&ctx->lane_meta, 16 * B * (size_t)ct.n_chunks * kLanes},
+        {(void**)&ctx->codec_errs, 3 * sizeof(unsigned long long)},
+    };
+    for (auto& w : want) {
+        if (*w.p) continue;
+        const hipError_t e = hipMalloc(w.p, w.bytes);
+        if (e != hipSuccess) { *w.p = nullptr; g_last_hip = (int)e; return e == hipErrorOutOfMemory ? IODF_E_NOMEM : IODF_E_HIP; }
+        ctx->workspace_bytes += w.bytes;
+    }
+    HIP_TRY(hipMemcpy(ctx->codec_sig, sig.data(), sizeof(int32_t) * kSigEntries, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(ctx->codec_inv, inv.data(), sizeof(int64_t) * 256, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemset(ctx->codec_errs, 0, 3 * sizeof(unsigned long long)));
+    HIP_TRY(hipDeviceSynchronize());
+    ctx->codec_ready = true;
+    return IODF_OK;
+}
+
+int iodf_codec_tables(int32_t* sig_host, int64_t* inv_host) {
+    if (!sig_host || !inv_host) return IODF_E_ARG;
+    codec_make_tables(sig_host, inv_host);
+    return IODF_OK;
+}
+
+int iodf_prior_cf(iodf_ctx* ctx, const int32_t* z_dev, const int8_t* codes_dev, int batch, int32_t* c_dev,
+                  int32_t* f_dev, void* stream) {
+    if (!ctx) return IODF_E_ARG;
+    if (batch < 0 || batch > ctx->max_batch) return IODF_E_BATCH;
+    if (batch == 0) return IODF_OK;
+    if (!z_dev || !c_dev || !f_dev) return IODF_E_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipSetDevice(ctx->device));
+    const int rc = codec_prepare(ctx);
+    if (rc != IODF_OK) return rc;
+    const CodecTables t{ctx->codec_sig, ctx->codec_inv};
+    PROF_LAUNCH(ctx, st, CLS_PRIOR_CF, 0, (long long)batch * (12 * ctx->d + ctx->d_codes),
+                launch_prior_cf(t, ctx->chunks, z_dev, ctx->d, ctx->d_codes ? codes_dev : nullptr, ctx->d_codes, batch,
+                                c_dev, f_dev, ctx->codec_errs, st));
+    return IODF_OK;
+}
+
+int iodf_encode(iodf_ctx* ctx, const uint8_t* x_dev, int batch, uint32_t* words_dev, int64_t cap_words,
+                uint32_t* sizes_dev, void* stream) {
+    if (!ctx) return IODF_E_ARG;
+    if (batch < 0 || batch > ctx->max_batch) return IODF_E_BATCH;
+    if (batch == 0) return IODF_OK;
+    if (!x_dev || !words_dev || !sizes_dev || cap_words < 1) return IODF_E_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipSetDevice(ctx->device));
+    int rc = codec_prepare(ctx);
+    if (rc != IODF_OK) return rc;
+    // the flow, into the compressor's own latent and code buffers
+    rc = iodf_forward(ctx, x_dev, batch, ctx->codec_z, ctx->d_codes ? ctx->codec_codes : nullptr, stream);
+    if (rc != IODF_OK) return rc;
+    const CodecTables t{ctx->codec_sig, ctx->codec_inv};
+    const int8_t* codes = ctx->d_codes ? ctx->codec_codes : nullptr;
+    PROF_LAUNCH(ctx, st, CLS_RANS_ENCODE, 0, (long long)batch * (4 * ctx->d + ctx->d_codes),
+                launch_rans_encode(t, ctx->chunks, ctx->codec_z, ctx->d, codes, ctx->d_codes, batch, ctx->lane_words,
+                                   ctx->lane_words_per_image, ctx->lane_meta, ctx->codec_errs, st));
+    PROF_LAUNCH(ctx, st, CLS_RANS_PACK, 0, 0,
+                launch_rans_pack(ctx->chunks, ctx->lane_words, ctx->lane_words_per_image, ctx->lane_meta, batch,
+                                 words_dev, cap_words, sizes_dev, ctx->codec_errs, st));
+    return IODF_OK;
+}
+
+// Decoding interleaves coder and flow: the latents of a level can be read only after the deeper
+// levels are inverted, because the head that parameterises their prior reads the half of the
+// level's state that continued downwards.
+int iodf_decode(iodf_ctx* ctx, const uint32_t* words_dev, int64_t cap_words, int batch, uint8_t* x_dev, void* stream) {
+    if (!ctx) return IODF_E_ARG;
+    if (batch < 0 || batch > ctx->max_batch) return IODF_E_BATCH;
+    if (batch == 0) return IODF_OK;
+    if (!words_dev || !x_dev) return IODF_E_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipSetDevice(ctx->device));
+    int rc = codec_prepare(ctx);
+    if (rc != IODF_OK) return rc;
+    const HostModel& m = ctx->shape;
+    if (cap_words < 1 + 3LL * m.levels * kLanes) return IODF_E_ARG;  // not even a header
+    const CodecTables t{ctx->codec_sig, ctx->codec_inv};
+    for (int lv = m.levels; lv >= 1; --lv) {
+        const int C = level_channels(lv), h = m.H >> lv, w = m.W >> lv;
+        const int n0 = ctx->first_net[lv];
+        const int32_t* phi = (const int32_t*)(ctx->params + ctx->nets[n0 + m.couplings - 1].phi_off);
+        const bool last = lv == m.levels;
+        const bool head = !last && m.has_heads;
+        if (head) {
+            // kept half back from the deeper level (the emitted half still holds stale values),
+            // then the head on it gives this level's codes
+            PROF_LAUNCH(ctx, st, CLS_UNFACTOR, 0, 8LL * batch * C * h * w,
+                        launch_unfactor(ctx->state[lv], batch, h, w, C, phi, C / 2, ctx->codec_z, ctx->d, ctx->z_off[lv],
+                                        ctx->state[lv + 1], st));
+            rc = run_net(ctx, ctx->nets[n0 + m.couplings], batch, +1, ctx->codec_codes, st);
+            if (rc != IODF_OK) return rc;
+        }
+        PROF_LAUNCH(ctx, st, CLS_RANS_DECODE, 0, (long long)batch * 5 * ctx->chunks.n[lv - 1],
+                    launch_rans_decode_chunk(t, ctx->chunks, lv - 1, words_dev, cap_words, batch,
+                                             head ? ctx->codec_codes : nullptr, ctx->d_codes, ctx->codec_z, ctx->d,
+                                             ctx->codec_errs, st));
+        PROF_LAUNCH(ctx, st, CLS_UNFACTOR, 0, 8LL * batch * C * h * w,
+                    launch_unfactor(ctx->state[lv], batch, h, w, C, phi, last ? 0 : C / 2, ctx->codec_z, ctx->d,
+                                    ctx->z_off[lv], last ? nullptr : ctx->state[lv + 1], st));
+        for (int k = m.couplings - 1; k >= 0; --k) {
+            rc = run_net(ctx, ctx->nets[n0 + k], batch, -1, nullptr, st);
+            if (rc != IODF_OK) return rc;
+        }
+    }
+    PROF_LAUNCH(ctx, st, CLS_EMIT_X, 0, 5LL * batch * ctx->d,
+                launch_emit_x(ctx->state[1], batch, m.H, m.W, x_dev, ctx->range_errs, st));
+    return IODF_OK;
+}
+
 int iodf_profile_begin(iodf_ctx* ctx, int max_launches) {
     if (!ctx || max_launches < 1 || max_launches > (1 << 22)) return IODF_E_ARG;
     if (ctx->prof_on) return IODF_E_ARG;
@@ -997,6 +1158,21 @@ int iodf_query(iodf_ctx* ctx, int what, int64_t* out) {
             unsigned long long v = 0;
             HIP_TRY(hipMemcpy(&v, ctx->range_errs, sizeof(v), hipMemcpyDeviceToHost));
             HIP_TRY(hipMemset(ctx->range_errs, 0, sizeof(v)));
+            *out = (int64_t)v;
+            return IODF_OK;
+        }
+        case IODF_Q_CODEC_HEADER_WORDS: *out = 1 + 3LL * ctx->shape.levels * kLanes; return IODF_OK;
+        case IODF_Q_CODEC_MAX_WORDS: *out = 1 + 3LL * ctx->shape.levels * kLanes + ctx->d; return IODF_OK;
+        case IODF_Q_CODEC_CLAMPED:
+        case IODF_Q_CODEC_OVERFLOWS:
+        case IODF_Q_CODEC_BROKEN_LANES: {
+            if (!ctx->codec_ready) { *out = 0; return IODF_OK; }
+            HIP_TRY(hipSetDevice(ctx->device));
+            HIP_TRY(hipDeviceSynchronize());
+            unsigned long long* p = ctx->codec_errs + (what - IODF_Q_CODEC_CLAMPED);
+            unsigned long long v = 0;
+            HIP_TRY(hipMemcpy(&v, p, sizeof(v), hipMemcpyDeviceToHost));
+            HIP_TRY(hipMemset(p, 0, sizeof(v)));
             *out = (int64_t)v;
             return IODF_OK;
         }

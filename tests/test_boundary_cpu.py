@@ -84,3 +84,17 @@ def test_null_context_is_refused():
     v = ctypes.c_int64(0)
     assert lib.iodf_query(None, 0, ctypes.byref(v)) == -1
     lib.iodf_free(None)
+
+
+def test_codec_tables_of_the_library_are_the_correctly_rounded_ones():
+    # host-only entry point; the library builds its tables with its own code, the oracle with
+    # its own, and the oracle's are pinned to 50-digit arithmetic elsewhere
+    import oracle
+    sig, inv = iodf.iodf_codec_tables()
+    osig, oinv = oracle.prior_tables()
+    assert np.array_equal(sig, osig) and np.array_equal(inv, oinv)
+    lib = iodf.load_library()
+    assert lib.iodf_codec_tables(None, None) == -1
+    assert lib.iodf_encode(None, None, 1, None, 10, None, None) == -1
+    assert lib.iodf_decode(None, None, 10, 1, None, None) == -1
+    assert lib.iodf_prior_cf(None, None, None, 1, None, None, None) == -1
