@@ -37,6 +37,7 @@ def main():
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
     ap.add_argument("--latency", action="store_true",
                     help="also report p50/p90 ms per call over the timed steps (each call synchronised)")
+    ap.add_argument("--no-codec", action="store_true", help="skip the compressor leg (flow + prior + rANS)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain 1 GiB device copy (calibrates HBM byte counters) and exit")
     args = ap.parse_args()
@@ -159,6 +160,47 @@ def main():
                         share_of_step=round(dom["total_ms"] / (1e3 * elapsed), 4),
                         instrumented_ms_per_step=round(1e3 * prof_elapsed / args.steps, 3))
 
+    # compressor leg: iodf_encode = the encode path above + prior masses + rANS containers;
+    # iodf_decode = rANS decode interleaved with the inverse flow and the heads
+    codec = None
+    if not args.no_codec and args.direction == "forward":
+        cap = flow.query(iodf.IODF_Q_CODEC_MAX_WORDS)
+        words = torch.zeros((batch, cap), dtype=torch.int32, device="cuda")
+        sizes = torch.zeros((batch,), dtype=torch.int32, device="cuda")
+        x_dec = torch.empty_like(x)
+        for _ in range(max(1, args.warmup)):
+            flow.encode(x, words=words, sizes=sizes)
+            flow.decode(words, x=x_dec)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            flow.encode(x, words=words, sizes=sizes)
+        torch.cuda.synchronize()
+        t_enc = (time.perf_counter() - t1) / args.steps
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            flow.decode(words, x=x_dec)
+        torch.cuda.synchronize()
+        t_dec = (time.perf_counter() - t1) / args.steps
+        ok = bool(torch.equal(x_dec, x)) and flow.codec_errors() == (0, 0, 0)
+        kstats = []
+        if not args.no_profile:
+            flow.profile_begin(4 * launches + 512)
+            flow.encode(x, words=words, sizes=sizes)
+            flow.decode(words, x=x_dec)
+            torch.cuda.synchronize()
+            for s in flow.profile_end():
+                if s["name"].startswith(("k_rans", "k_prior")):
+                    kstats.append(dict(name=s["name"], launches=s["launches"], total_ms=round(s["total_ms"], 4),
+                                       alg_gbs=round(s["bytes"] / (s["total_ms"] * 1e-3) / 1e9, 2)))
+        comp_bytes = 4.0 * float(sizes.sum().item())
+        codec = dict(encode_images_per_s=round(batch / t_enc, 2), decode_images_per_s=round(batch / t_dec, 2),
+                     encode_ms=round(1e3 * t_enc, 3), decode_ms=round(1e3 * t_dec, 3),
+                     raw_MB_per_s_encode=round(batch * flow.d / t_enc / 1e6, 1),
+                     bits_per_dim=round(8.0 * comp_bytes / (batch * flow.d), 4), round_trip_exact=ok,
+                     note="random-weight model: bits/dim says nothing about compression quality",
+                     coder_kernels=kstats)
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -193,6 +235,7 @@ def main():
         "whole_path_frac_of_int8_peak": round(whole_tops / INT8_PEAK_TOPS, 4),
         "round_trip_exact": round_trip,
         "latency": latency,
+        "codec": codec,
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,

@@ -82,3 +82,41 @@ def test_cfg5_batch1(capsys):
 def test_cfg5_batch1024_sampled(capsys):
     # throughput shape; oracle on sampled images, batch invariance on the others
     _sampled(capsys, "cfg5", 1024, sample=(0, 300, 777, 1023), invariance=(1, 511), chunk=301)
+
+
+def _codec_full(capsys, name, batch, sample):
+    """Compressor at full size: every image must decode back exactly; sampled containers are
+    compared with the oracle's word for word."""
+    import torch
+
+    def say(*a):
+        with capsys.disabled():
+            print("[full-size codec]", *a, flush=True)
+
+    flow = gpu_flow(name, max_batch=batch)
+    x = images(name, batch=batch)
+    xg = to_gpu(x)
+    words, sizes = flow.encode(xg)
+    torch.cuda.synchronize()
+    say(name, "batch", batch, "encoded; mean bits/dim %.3f" % (32.0 * float(sizes.float().mean()) / flow.d))
+    x2 = flow.decode(words)
+    torch.cuda.synchronize()
+    assert torch.equal(x2, xg), "codec round trip"
+    assert flow.codec_errors() == (0, 0, 0) and flow.range_errors() == 0
+    wc, sc = words.cpu().numpy().view(np.uint32), sizes.cpu().numpy().view(np.uint32)
+    flow.close()
+    om = oracle_model(name)
+    for i in sample:
+        ref, ref_sizes, cl = om.encode(x[i:i + 1])
+        say("oracle container", i, "done:", int(ref_sizes[0]), "words")
+        assert cl == 0 and ref_sizes[0] == sc[i] and np.array_equal(ref[0], wc[i]), "container %d" % i
+
+
+@pytest.mark.timeout(900)
+def test_cfg4_codec(capsys):
+    _codec_full(capsys, "cfg4", CONFIGS["cfg4"].batch, sample=(5, 100))
+
+
+@pytest.mark.timeout(900)
+def test_cfg5_codec_batch1024(capsys):
+    _codec_full(capsys, "cfg5", 1024, sample=(13, 1000))
