@@ -56,6 +56,9 @@ struct ConvArgs {
     const int32_t* mul;
     const int32_t* shift;  // rq_fast: shift - 32 (every shift of the layer is >= 33); else the shift itself
     int rq_fast;
+    // rq_fast only: smallest accumulator (bias included) whose requantised value reaches 127, saturated
+    // to INT32_MAX; lets a ReLU layer clamp before the multiply instead of after it
+    const int32_t* clamp_hi;
     int32_t* partial;  // optional split-K scratch: int32 [npix][n_pad], all zero between launches
     int n_store;   // channels written (<= n_pad); multiple of 4 in MODE_ACT without out_map
     int mode;

@@ -85,13 +85,18 @@ __device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc
     }
     static_for<TC>([&](auto tc_) {
         constexpr int tc = decltype(tc_)::value;
-        v4i Bq[4], Mq[4], Sq[4];  // bias, multiplier, shift - 32 of this lane's 16 channels (staged in LDS)
+        // bias (PURE_RELU: the clamp bound instead), multiplier, shift - 32 of this lane's 16 channels
+        // (staged in LDS), and the rounding constant 2^(shift - 33)
+        v4i Bq[4], Mq[4], Sq[4];
+        unsigned Rq[4][4];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int nl = ch_local + tc * 32 + g * 8 + half * 4;
             Bq[g] = *(const v4i*)(cst + nl);
             Mq[g] = *(const v4i*)(cst + cst_n + nl);
             Sq[g] = *(const v4i*)(cst + 2 * cst_n + nl);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) Rq[g][e] = 1u << (Sq[g][e] - 1);
         }
         static_for<TP>([&](auto tp_) {
             constexpr int tp = decltype(tp_)::value;
@@ -105,13 +110,27 @@ __device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc
                 constexpr int g = decltype(g_)::value;
                 int y[4];
                 if constexpr (PURE_RELU) {
-                    // ReLU without shortcut: negative accumulators end at 0 whatever their magnitude
+                    // ReLU without shortcut. The accumulators already hold the bias. Clamping them to
+                    // [0, hi] first (hi = the smallest value that requantises to 127; the rescale is
+                    // monotone and steps by at most 1) replaces both the ReLU and the saturation, so
+                    // every result fits a byte and the last shift can drop it straight into its place
+                    // in the packed dword.
+                    unsigned q[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const int av = acc[tc][tp][g * 4 + e] + Bq[g][e];
-                        const int r = rq_fast_abs((unsigned)(av < 0 ? 0 : av), Mq[g][e], Sq[g][e]);
-                        y[e] = r > 127 ? 127 : r;
+                        int av;
+                        asm("v_med3_i32 %0, %1, 0, %2" : "=v"(av) : "v"(acc[tc][tp][g * 4 + e]), "v"(Bq[g][e]));
+                        q[e] = __umulhi((unsigned)av, (unsigned)Mq[g][e]) + Rq[g][e];
                     }
+                    unsigned p4 = q[0] >> Sq[g][0];
+                    asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD "
+                        "src1_sel:DWORD" : "+v"(p4) : "v"(Sq[g][1]), "v"(q[1]));
+                    asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD "
+                        "src1_sel:DWORD" : "+v"(p4) : "v"(Sq[g][2]), "v"(q[2]));
+                    asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD "
+                        "src1_sel:DWORD" : "+v"(p4) : "v"(Sq[g][3]), "v"(q[3]));
+                    pk[g] = p4;
+                    return;
                 } else {
                     int sc = 0;
                     if (a.shortcut && live) sc = *(const int*)(orow + g * 8 + half * 4);
@@ -325,10 +344,26 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
             for (int r = 0; r < 16; ++r) acc[tc][tp][r] = 0;
         });
     });
-    int* const cst = (int*)(lds + NST * STAGE);  // [3][BC]: bias, multiplier, shift
+    if constexpr (EPI == EPI_FAST_RELU) {
+        // this epilogue clamps before it rescales, so the bias has to be in the accumulators
+        // from the start: register quad g of tile tc holds channels tc*32 + g*8 + half*4 .. +3
+        static_for<TC>([&](auto tc_) {
+            constexpr int tc = decltype(tc_)::value;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const v4i b4 = *(const v4i*)(a.bias + c0 + wc * WTC + tc * 32 + g * 8 + half * 4);
+                static_for<TP>([&](auto tp_) {
+                    constexpr int tp = decltype(tp_)::value;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[tc][tp][g * 4 + e] = b4[e];
+                });
+            }
+        });
+    }
+    int* const cst = (int*)(lds + NST * STAGE);  // [3][BC]: bias (or clamp bound), multiplier, shift
     int cb_v = 0, cm_v = 0, cs_v = 0;
     if (tid < BC) {
-        cb_v = a.bias[c0 + tid];
+        cb_v = EPI == EPI_FAST_RELU ? a.clamp_hi[c0 + tid] : a.bias[c0 + tid];
         cm_v = a.mul[c0 + tid];
         cs_v = a.shift[c0 + tid];
     }
@@ -583,7 +618,7 @@ hipError_t launch_conv(const ConvArgs& a, hipStream_t stream) {
     const int npb = (a.npix + t.bp - 1) / t.bp, ncb = a.n_pad / t.bc;
     const int grid = ((npb + 7) / 8) * 8 * ncb;
     const bool fast = a.mode == MODE_ACT && !a.out_map && a.rq_fast && a.n_store % 16 == 0;
-    const int epi = !fast ? EPI_ANY : (a.relu && !a.shortcut) ? EPI_FAST_RELU : EPI_FAST;
+    const int epi = !fast ? EPI_ANY : (a.relu && !a.shortcut && a.clamp_hi) ? EPI_FAST_RELU : EPI_FAST;
     const int splits = conv_pick_splits(a, best);
     hipLaunchKernelGGL(t.kern[epi], dim3(grid, splits), dim3(t.threads), t.lds, stream, a, npb, ncb);
     hipError_t e = hipGetLastError();

@@ -7,6 +7,7 @@
 
 #include <algorithm>
 #include <array>
+#include <climits>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -193,6 +194,7 @@ struct DevLayer {
     int in_buf, in_off;    // input tensor: buffer and first channel (multiple of 64)
     int out_buf, out_off;  // output tensor (MODE_ACT)
     size_t wgt_off, bias_off, mul_off, shift_off;  // byte offsets into the parameter arena
+    size_t hi_off = (size_t)-1;                    // rq_fast layers: clamp bound per channel
     size_t map_off;                                // (size_t)-1 when there is no scatter map
     // tap-expanded 3x3 last layer (see TapSumArgs): the GEMM is 1x1 with 9 * c_out rows and
     // stores raw accumulators; these are the constants of the summing pass
@@ -283,6 +285,22 @@ void pack_layer(Arena& A, const HostLayer& L, const std::vector<int>& rows, cons
     for (int n = 0; n < D.n_pad; ++n) {
         if (n >= (int)rows.size()) { mul[n] = 0; sh[n] = D.rq_fast ? 33 : 0; }
         if (D.rq_fast) sh[n] -= 32;
+    }
+    if (D.rq_fast) {
+        // Smallest accumulator a >= 0 with (floor(a * M / 2^32) + 2^(sh-1)) >> sh >= 127, i.e.
+        // a * M >= (127 * 2^sh - 2^(sh-1)) * 2^32. The rescale factor M / 2^(32+sh) is below 1, so the
+        // result there is exactly 127; beyond int32 no accumulator reaches 127 at all.
+        D.hi_off = A.alloc(4 * (size_t)D.n_pad);
+        int32_t* hi = (int32_t*)(A.host.data() + D.hi_off);
+        mul = (int32_t*)(A.host.data() + D.mul_off);  // the arena may have moved
+        sh = (int32_t*)(A.host.data() + D.shift_off);
+        for (int n = 0; n < D.n_pad; ++n) {
+            hi[n] = INT32_MAX;
+            if (mul[n] <= 0) continue;
+            const unsigned __int128 need = ((unsigned __int128)((127ULL << sh[n]) - (1ULL << (sh[n] - 1)))) << 32;
+            const unsigned __int128 a = (need + (unsigned)mul[n] - 1) / (unsigned)mul[n];
+            if (a < (unsigned __int128)INT32_MAX) hi[n] = (int32_t)(uint64_t)a;
+        }
     }
     D.macs_per_pixel = (long long)rows.size() * live * taps;
     D.bytes_per_pixel = (long long)live + (long long)rows.size();
@@ -566,6 +584,7 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
         a.shift = (const int32_t*)(ctx->params + L.shift_off);
         a.n_store = L.n_store;
         a.rq_fast = L.rq_fast;
+        a.clamp_hi = L.hi_off == (size_t)-1 ? nullptr : (const int32_t*)(ctx->params + L.hi_off);
         if (L.mode != MODE_ACT && (size_t)npix * L.n_pad <= ctx->partial_elems) a.partial = ctx->partial;
         a.mode = L.mode;
         a.relu = L.relu;
