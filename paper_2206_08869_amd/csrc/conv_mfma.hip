@@ -56,6 +56,24 @@ __device__ __forceinline__ int rq_dev(int acc, int M, int s) {
 
 __device__ __forceinline__ int sat8_dev(int v) { return v > 127 ? 127 : (v < -128 ? -128 : v); }
 
+// Pixel index m -> position of the pixel in the zero-bordered image stack, (b * PP + (i+1) * W2 + (j+1)).
+// Image sides that are powers of two (every benchmark shape) take shifts; others divide.
+__device__ __forceinline__ int bordered_pos(const ConvArgs& a, int m, int hw, int W2, int PP) {
+    int b, i, j;
+    if (a.log2_w >= 0 && a.log2_hw >= 0) {
+        b = m >> a.log2_hw;
+        const int q = m & (hw - 1);
+        i = q >> a.log2_w;
+        j = q & (a.w - 1);
+    } else {
+        b = m / hw;
+        const int q = m - b * hw;
+        i = q / a.w;
+        j = q - i * a.w;
+    }
+    return b * PP + (i + 1) * W2 + (j + 1);
+}
+
 // Fast exact requantise for shifts >= 33: with u = |acc| * M = hi * 2^32 + lo, the rounding
 // constant 2^(s-1) is a multiple of 2^32, so floor((u + 2^(s-1)) / 2^s) =
 // (hi + 2^(s-33)) >> (s-32) and the low word never matters. sh = s - 32 (1..30).
@@ -80,8 +98,7 @@ __device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc
     for (int tp = 0; tp < TP; ++tp) {
         int m = pix_base + tp * 32 + l32;
         m = m < a.npix ? m : 0;
-        const int b = m / hw, q = m - b * hw, i = q / a.w, j = q - i * a.w;
-        ppos[tp] = (long long)(b * PP + (i + 1) * W2 + (j + 1)) * 64;
+        ppos[tp] = (long long)bordered_pos(a, m, hw, W2, PP) * 64;
     }
     static_for<TC>([&](auto tc_) {
         constexpr int tc = decltype(tc_)::value;
@@ -324,8 +341,7 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
     for (int u = 0; u < AI; ++u) {
         int m = p0 + (wave * AI + u) * 16 + lrow;
         m = m < a.npix ? m : a.npix - 1;
-        const int b = m / hw, q = m - b * hw, i = q / a.w, j = q - i * a.w;
-        aoffl[u] = (unsigned)(b * PP + (i + 1) * W2 + (j + 1)) * KT + (unsigned)(lpart * 16);
+        aoffl[u] = (unsigned)bordered_pos(a, m, hw, W2, PP) * KT + (unsigned)(lpart * 16);
     }
     const int8_t* const wbase = a.wgt + (long long)(c0 + wave * WI * 16) * KT;
     const int8_t* const abase = a.in + (long long)a.in_chunk0 * a.in_plane;
@@ -610,7 +626,13 @@ int conv_pick_splits(const ConvArgs& a, int tile) {
     return s < 2 ? 1 : (int)s;
 }
 
-hipError_t launch_conv(const ConvArgs& a, hipStream_t stream) {
+hipError_t launch_conv(const ConvArgs& a_in, hipStream_t stream) {
+    ConvArgs a = a_in;
+    {
+        auto lg = [](int v) { int l = 0; while ((1 << l) < v) ++l; return (1 << l) == v ? l : -1; };
+        a.log2_w = lg(a.w);
+        a.log2_hw = a.log2_w >= 0 ? lg(a.h * a.w) : -1;
+    }
     if (a.npix <= 0) return hipSuccess;
     const int best = conv_pick_tile(a);
     if (best < 0) return hipErrorInvalidValue;
