@@ -205,7 +205,8 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         om = oracle.Model(blob)
-        n_img = 1 if macs_img > 5e10 else min(batch, max(1, int(2e11 // max(macs_img, 1))))
+        # about 15 s of host work: the oracle sustains roughly 7e10 MAC/s on the box's 16 cores
+        n_img = min(batch, max(1, int(round(15 * 7e10 / max(macs_img, 1)))))
         t0 = time.perf_counter()
         if args.direction == "forward":
             z_ref, c_ref = om.forward(x_host[:n_img])

@@ -244,8 +244,11 @@ struct Arena {
 // Append one layer's packed weights and constants to the arena.
 //   rows:   original output channels kept, in order
 //   colpos: packed input column of each original input channel, or -1
+//   masked: rows whose gate is 0 stay in place as all-zero filters with zero bias and multiplier
+//           (they output exactly 0, as a removed filter does) instead of being removed; `rows`
+//           then lists every channel. Used where the consumer needs the full width anyway.
 void pack_layer(Arena& A, const HostLayer& L, const std::vector<int>& rows, const std::vector<int>& colpos, int cin_pad,
-                DevLayer& D) {
+                DevLayer& D, bool masked = false) {
     const int taps = L.k * L.k;
     D.taps = taps;
     D.cin_pad = cin_pad;
@@ -264,8 +267,11 @@ void pack_layer(Arena& A, const HostLayer& L, const std::vector<int>& rows, cons
     int32_t* sh = (int32_t*)(A.host.data() + D.shift_off);
     int live = 0;
     for (int c = 0; c < L.C_in; ++c) live += colpos[c] >= 0;
+    int kept = 0;
     for (size_t n = 0; n < rows.size(); ++n) {
         const int r = rows[n];
+        if (masked && !L.gate[r]) { bias[n] = 0; mul[n] = 0; sh[n] = 33; continue; }
+        ++kept;
         const int8_t* src = L.W + (size_t)r * L.C_in * taps;
         // input column pc, tap t goes to k-tile (pc / 64) * taps + t, row n, byte pc % 64
         for (int c = 0; c < L.C_in; ++c) {
@@ -302,10 +308,10 @@ void pack_layer(Arena& A, const HostLayer& L, const std::vector<int>& rows, cons
             if (a < (unsigned __int128)INT32_MAX) hi[n] = (int32_t)(uint64_t)a;
         }
     }
-    D.macs_per_pixel = (long long)rows.size() * live * taps;
-    D.bytes_per_pixel = (long long)live + (long long)rows.size();
+    D.macs_per_pixel = (long long)kept * live * taps;
+    D.bytes_per_pixel = (long long)live + (long long)kept;
     D.wgt_bytes = D.macs_per_pixel;
-    D.wide = rows.size() >= 128 && live >= 128;
+    D.wide = kept >= 128 && live >= 128;
 }
 
 // Last layer of a network, 3x3 with few output channels, as a 1x1 GEMM over 9 * C_out rows.
@@ -406,21 +412,16 @@ void plan_net(Arena& A, const HostModel& m, const HostNet& N, DevNet& D, int buf
         const int rw = round64(Wd);
         D.a_stride = rw;
         buf_w[BUF_A] = std::max(buf_w[BUF_A], rw);
-        auto stream_out = [&](const HostLayer& H, DevLayer& d, const std::vector<int>& rows) {
-            if ((int)rows.size() == Wd) {
-                d.n_store = rw;
-            } else {  // scatter-add into the unpruned stream through the kept-index list
-                d.n_store = (int)rows.size();
-                d.map_off = put_map(A, rows, d.n_pad);
-            }
-            (void)H;
-        };
+        // The stream keeps its full width (the shortcut adds into unpruned channels, Sec. 4.4), so
+        // the layers that write it keep gated-off filters as zero rows: a zero row adds 0 to the
+        // shortcut exactly like a removed one, and the store stays a plain full-width one.
+        std::vector<int> all_rows(Wd);
+        for (int c = 0; c < Wd; ++c) all_rows[c] = c;
         {
-            const std::vector<int> r0 = kept_rows(L[0]);
-            pack_layer(A, L[0], r0, identity_map(N.C_in), D.cin_pad0, D.layers[0]);
+            pack_layer(A, L[0], all_rows, identity_map(N.C_in), D.cin_pad0, D.layers[0], true);
             io(D.layers[0], BUF_XQ, 0, D.cin_pad0, BUF_A, 0, rw, MODE_ACT);
-            stream_out(L[0], D.layers[0], r0);
-            D.zero_a = (int)r0.size() != Wd;
+            D.layers[0].n_store = rw;
+            D.zero_a = false;
         }
         for (int l = 1; l + 1 < nl; l += 2) {
             const std::vector<int> r1 = kept_rows(L[l]);
@@ -429,10 +430,9 @@ void plan_net(Arena& A, const HostModel& m, const HostNet& N, DevNet& D, int buf
             pack_layer(A, L[l], r1, identity_map(Wd), rw, D.layers[l]);
             io(D.layers[l], BUF_A, 0, rw, BUF_B, 0, tw, MODE_ACT);
             D.layers[l].n_store = tw;
-            const std::vector<int> r2 = kept_rows(L[l + 1]);
-            pack_layer(A, L[l + 1], r2, rank_map(L[l], 0), tw, D.layers[l + 1]);
+            pack_layer(A, L[l + 1], all_rows, rank_map(L[l], 0), tw, D.layers[l + 1], true);
             io(D.layers[l + 1], BUF_B, 0, tw, BUF_A, 0, rw, MODE_ACT);
-            stream_out(L[l + 1], D.layers[l + 1], r2);
+            D.layers[l + 1].n_store = rw;
         }
         plan_last(L[nl - 1], identity_map(Wd), rw, D.layers[nl - 1]);
         D.layers[nl - 1].in_buf = BUF_A; D.layers[nl - 1].in_off = 0; D.layers[nl - 1].out_buf = -1;

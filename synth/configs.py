@@ -26,6 +26,11 @@ class FlowConfig:
     keep: float = 1.0       # fraction of filters kept by the binary gates
     image_kind: str = "filtered"   # "filtered" | "uniform"
     seed_id: int = 0
+    block_k2: int = 1       # resnet family: kernel of a block's second conv (the paper's own blocks use 3)
+    keep_levels: tuple = () # per-level keep fractions (level 1 first); empty = `keep` everywhere
+
+    def keep_at(self, level):
+        return self.keep_levels[level - 1] if self.keep_levels else self.keep
 
     def level_channels(self, level):
         """Channels of the flow state at 1-based `level` (after its squeeze)."""
@@ -56,11 +61,11 @@ class FlowConfig:
         return replace(self, batch=b)
 
 
-def net_layers(family, c_in, c_out, width, depth):
+def net_layers(family, c_in, c_out, width, depth, k2=1):
     """Layer list of one network: tuples (C_out, C_in, k, relu, shortcut, gated).
 
     plain : conv3x3 -> ReLU -> conv3x3
-    resnet: conv_in, depth x [conv3x3 ReLU, conv1x1 + shortcut ReLU], conv_out
+    resnet: conv_in, depth x [conv3x3 ReLU, conv k2 x k2 + shortcut ReLU], conv_out
     dense : conv_in, depth x [conv1x1 over all features so far, conv3x3], conv_out
             over the concatenation of all features
     Only convolutions that produce hidden features carry gates.
@@ -73,7 +78,7 @@ def net_layers(family, c_in, c_out, width, depth):
         L.append((width, c_in, 3, True, False, True))
         for _ in range(depth):
             L.append((width, width, 3, True, False, True))
-            L.append((width, width, 1, True, True, True))
+            L.append((width, width, k2, True, True, True))
         L.append((c_out, width, 3, False, False, False))
     elif family == DENSE:
         L.append((width, c_in, 3, True, False, True))
@@ -104,15 +109,14 @@ def flow_networks(cfg):
 
 def macs_per_image(cfg, with_heads=True, kept_only=True):
     """Multiply-accumulates of one forward pass for one image, at true channel counts."""
-    keep = cfg.keep if kept_only else 1.0
     total = 0
     for kind, lv, c, c_in, c_out in flow_networks(cfg):
         if kind == 1 and not with_heads:
             continue
         h, w = cfg.level_hw(lv)
-        wk = int(round(cfg.width * keep))
+        wk = max(1, int(round(cfg.width * cfg.keep_at(lv)))) if kept_only and cfg.keep_at(lv) < 1.0 else cfg.width
         for i, (co, ci, k, relu, sc, gated) in enumerate(
-                net_layers(cfg.family, c_in, c_out, cfg.width, cfg.depth)):
+                net_layers(cfg.family, c_in, c_out, cfg.width, cfg.depth, cfg.block_k2)):
             co_k = wk if gated else co
             ci_k = ci if i == 0 else (ci // cfg.width) * wk
             total += co_k * ci_k * k * k * h * w
@@ -142,4 +146,13 @@ CONFIGS = {
     # image sides that are not powers of two and not square (levels 12x20 and 6x10)
     "rect_dense": FlowConfig("rect_dense", 24, 40, 3, 2, 2, DENSE, 64, 2, True, seed_id=13),
     "rect_resnet_g": FlowConfig("rect_resnet_g", 24, 40, 2, 2, 2, RESNET, 32, 2, False, keep=0.5, seed_id=14),
+    # The paper's own coupling network (App. B.1): conv_in, 8 residual blocks of two 3x3 convolutions at
+    # 128 channels, conv_out; L = 3 levels for 32x32 images, 4 for 64x64, 8 couplings per level; the pruned
+    # variant keeps fewer filters the deeper the level (Sec. 5.1, the pruning figure).
+    "paper_res32": FlowConfig("paper_res32", 32, 32, 512, 3, 8, RESNET, 128, 8, True, seed_id=15, block_k2=3),
+    "paper_res64": FlowConfig("paper_res64", 64, 64, 256, 4, 8, RESNET, 128, 8, True, seed_id=16, block_k2=3),
+    "paper_iodf64": FlowConfig("paper_iodf64", 64, 64, 256, 4, 8, RESNET, 128, 8, True, seed_id=17, block_k2=3,
+                               keep=0.5, keep_levels=(0.75, 0.625, 0.375, 0.25)),
+    "mini_paper_g": FlowConfig("mini_paper_g", 16, 16, 3, 2, 2, RESNET, 32, 3, True, seed_id=18, block_k2=3,
+                               keep=0.5, keep_levels=(0.75, 0.375)),
 }

@@ -76,7 +76,7 @@ def _rha(a):
 
 def _gen_network(cfg, seed, idx, kind, level, c_level, c_in, c_out, n_prev, mode, out):
     """Write network `idx` into the byte buffer `out` (its own slice of the blob)."""
-    layers = net_layers(cfg.family, c_in, c_out, cfg.width, cfg.depth)
+    layers = net_layers(cfg.family, c_in, c_out, cfg.width, cfg.depth, cfg.block_k2)
     pos = 0
 
     def put(arr):
@@ -129,8 +129,8 @@ def _gen_network(cfg, seed, idx, kind, level, c_level, c_in, c_out, n_prev, mode
             wq = np.zeros((co, fan_in), dtype=np.int8)
         # gates: exactly round(keep * C_out) filters survive in a gated layer
         gate = np.ones(co, dtype=np.uint8)
-        if gated and cfg.keep < 1.0:
-            n_keep = max(1, int(round(cfg.keep * co)))
+        if gated and cfg.keep_at(level) < 1.0:
+            n_keep = max(1, int(round(cfg.keep_at(level) * co)))
             order = prng.shuffle(prng.substream(lseed, 1), co)
             gate[:] = 0
             gate[order[:n_keep]] = 1
@@ -195,7 +195,7 @@ def make_blob(cfg, seed=None, mode="random", threads=None):
     """
     seed = (2000 + cfg.seed_id) if seed is None else seed
     nets = flow_networks(cfg)
-    sizes = [net_bytes(kind, c, net_layers(cfg.family, ci, co, cfg.width, cfg.depth))
+    sizes = [net_bytes(kind, c, net_layers(cfg.family, ci, co, cfg.width, cfg.depth, cfg.block_k2))
              for (kind, lv, c, ci, co) in nets]
     offs = np.concatenate([[64], 64 + np.cumsum(sizes)]).astype(np.int64)
     blob = np.zeros(int(offs[-1]), dtype=np.uint8)

@@ -72,6 +72,18 @@ def test_cfg4_sampled(capsys):
     _sampled(capsys, "cfg4", CONFIGS["cfg4"].batch, sample=(0, 77, 127), invariance=(64,), chunk=37)
 
 
+@pytest.mark.timeout(600)
+def test_paper_network_pruned_sampled(capsys):
+    # the paper's own coupling network (8 residual blocks of 3x3 convolutions at 128 channels), pruned
+    # hardest at the deepest level; compacted widths 96 / 80 / 48 / 32 are padded to 64-channel planes
+    _sampled(capsys, "paper_iodf64", CONFIGS["paper_iodf64"].batch, sample=(0, 101, 255), invariance=(3,), chunk=71)
+
+
+@pytest.mark.timeout(600)
+def test_paper_network_32_sampled(capsys):
+    _sampled(capsys, "paper_res32", CONFIGS["paper_res32"].batch, sample=(0, 300, 511), invariance=(9,), chunk=129)
+
+
 @pytest.mark.timeout(900)
 def test_cfg5_batch1(capsys):
     # latency shape: batch 1, the whole image against the oracle

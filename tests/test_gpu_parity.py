@@ -37,7 +37,7 @@ def _check_full(name, batch=None, kinds=("filtered",), modes=("random",)):
 
 
 @pytest.mark.parametrize("name", ["cfg1", "mini_resnet", "mini_dense", "mini_dense_g", "mini_resnet_g",
-                                  "odd_dense_g", "rect_dense", "rect_resnet_g"])
+                                  "odd_dense_g", "rect_dense", "rect_resnet_g", "mini_paper_g"])
 def test_small_flows_match_oracle(name):
     _check_full(name, kinds=("filtered", "uniform"))
 

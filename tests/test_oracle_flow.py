@@ -335,13 +335,13 @@ def test_gate_mask_equals_manual_deletion(name):
 
 
 def test_gate_keep_fraction_is_exact():
-    for name in ("mini_dense_g", "odd_dense_g", "mini_resnet_g"):
+    for name in ("mini_dense_g", "odd_dense_g", "mini_resnet_g", "mini_paper_g"):
         cfg = CONFIGS[name]
         model = parse_blob(make_blob(cfg))
         for net in model["nets"]:
             for L in net["layers"]:
                 if L["flags"] & 4:
-                    assert int(L["gate"].sum()) == int(round(cfg.keep * L["gate"].size))
+                    assert int(L["gate"].sum()) == int(round(cfg.keep_at(net["level"]) * L["gate"].size))
                 else:
                     assert L["gate"].all()
 
