@@ -550,6 +550,7 @@ struct TileCfg {
 
 const TileCfg kTiles[] = {
     IODF_TILE(256, 256, 2, 4, 4),
+    IODF_TILE(128, 512, 2, 4, 3),
     IODF_TILE(128, 128, 4, 2, 4),
     IODF_TILE(64, 256, 1, 4, 4),
     IODF_TILE(64, 64, 2, 2, 4),
