@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--latency", action="store_true",
                     help="also report p50/p90 ms per call over the timed steps (each call synchronised)")
     ap.add_argument("--no-codec", action="store_true", help="skip the compressor leg (flow + prior + rANS)")
+    ap.add_argument("--large-image", default="1024x1024",
+                    help="HxW of the synthetic high-resolution image of the patch-coding leg ('' to skip)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain 1 GiB device copy (calibrates HBM byte counters) and exit")
     args = ap.parse_args()
@@ -200,6 +202,28 @@ def main():
                      bits_per_dim=round(8.0 * comp_bytes / (batch * flow.d), 4), round_trip_exact=ok,
                      note="random-weight model: bits/dim says nothing about compression quality",
                      coder_kernels=kstats)
+
+    # patch-based coding of one high-resolution image (Sec. 5.2): tile -> encode -> decode -> untile
+    if codec is not None and args.large_image:
+        from synth import make_large_image
+        ih, iw = (int(v) for v in args.large_image.lower().split("x"))
+        big = torch.from_numpy(make_large_image(ih, iw)).cuda()
+        parts = flow.encode_image(big)      # warm-up
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        parts = flow.encode_image(big)
+        torch.cuda.synchronize()
+        t_e = time.perf_counter() - t1
+        t1 = time.perf_counter()
+        back = flow.decode_image(parts, ih, iw)
+        torch.cuda.synchronize()
+        t_d = time.perf_counter() - t1
+        comp = 4.0 * sum(float(p[1].sum().item()) for p in parts)
+        codec["patch_coding"] = dict(image="3x%dx%d u8" % (ih, iw), patches=flow.n_patches(ih, iw),
+                                     encode_MB_per_s=round(3.0 * ih * iw / t_e / 1e6, 2),
+                                     decode_MB_per_s=round(3.0 * ih * iw / t_d / 1e6, 2),
+                                     compressed_bytes=int(comp),
+                                     round_trip_exact=bool(torch.equal(back, big)) and flow.codec_errors() == (0, 0, 0))
 
     cpu = None
     if not args.no_cpu_baseline:

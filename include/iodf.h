@@ -144,6 +144,20 @@ int iodf_decode(iodf_ctx* ctx, const uint32_t* words_dev, int64_t cap_words, int
 int iodf_codec_tables(int32_t* sig_host, int64_t* inv_host);
 
 /*
+ * Patch-based coding of images larger than the flow's H x W (Sec. 5.2: a large image is coded as
+ * a batch of patches). img_dev: device, planar uint8 [3][img_h][img_w]. The image is covered by a
+ * row-major grid of ceil(img_h/H) x ceil(img_w/W) patches; iodf_tile_patches writes patches
+ * first_patch .. first_patch + n_patches - 1 to x_dev (uint8 [n_patches][3][H][W], ready for
+ * iodf_forward / iodf_encode), reading 128 where a patch sticks out of the image;
+ * iodf_untile_patches copies decoded patches back, dropping what lies outside. Patches beyond the
+ * grid are an argument error.
+ */
+int iodf_tile_patches(iodf_ctx* ctx, const uint8_t* img_dev, int img_h, int img_w, int first_patch, int n_patches,
+                      uint8_t* x_dev, void* stream);
+int iodf_untile_patches(iodf_ctx* ctx, const uint8_t* x_dev, int first_patch, int n_patches, uint8_t* img_dev,
+                        int img_h, int img_w, void* stream);
+
+/*
  * Per-kernel timing for roofline reports (the paper reports latency only, Sec. 5.2; this is
  * measurement support, not part of the method). Between begin and end every kernel launch of
  * iodf_forward / iodf_inverse is bracketed by HIP events on the caller's stream (no

@@ -304,3 +304,34 @@ def codec_decode_chunk(cont, n, c, m=None, l=None):
     zc = np.zeros(int(n[c]), np.int32)
     rc = lib().orc_codec_decode_chunk(_p(cont), cont.size, n.size, _p(n), int(c), _p(m), _p(l), _p(zc))
     return zc, int(rc)
+
+
+# ---- patch-based coding of a large image (Sec. 5.2) ----
+
+def tile_patches(img, H, W, pad=128):
+    """Planar image [3,h,w] -> patches [n,3,H,W] of the row-major grid ceil(h/H) x ceil(w/W);
+    pixels outside the image are `pad`. Plain loops: this is the definition."""
+    img = np.asarray(img, np.uint8)
+    _, h, w = img.shape
+    ph, pw = -(-h // H), -(-w // W)
+    out = np.full((ph * pw, 3, H, W), pad, np.uint8)
+    for py in range(ph):
+        for px in range(pw):
+            y0, x0 = py * H, px * W
+            y1, x1 = min(h, y0 + H), min(w, x0 + W)
+            out[py * pw + px, :, :y1 - y0, :x1 - x0] = img[:, y0:y1, x0:x1]
+    return out
+
+
+def untile_patches(patches, h, w):
+    patches = np.asarray(patches, np.uint8)
+    n, _, H, W = patches.shape
+    ph, pw = -(-h // H), -(-w // W)
+    assert n == ph * pw
+    img = np.zeros((3, h, w), np.uint8)
+    for py in range(ph):
+        for px in range(pw):
+            y0, x0 = py * H, px * W
+            y1, x1 = min(h, y0 + H), min(w, x0 + W)
+            img[:, y0:y1, x0:x1] = patches[py * pw + px, :, :y1 - y0, :x1 - x0]
+    return img

@@ -23,7 +23,7 @@ IODF_Q_Z_ELEMS, IODF_Q_CODE_BYTES, IODF_Q_WORKSPACE_BYTES, IODF_Q_MACS_FORWARD, 
 
 EXPORTS = ["iodf_init", "iodf_forward", "iodf_inverse", "iodf_query", "iodf_free", "iodf_strerror",
            "iodf_last_hip_error", "iodf_profile_begin", "iodf_profile_end", "iodf_prior_cf", "iodf_encode",
-           "iodf_decode", "iodf_codec_tables"]
+           "iodf_decode", "iodf_codec_tables", "iodf_tile_patches", "iodf_untile_patches"]
 
 
 class KernelStat(ctypes.Structure):
@@ -89,6 +89,10 @@ def load_library(build_if_missing=True):
     L.iodf_decode.argtypes = [vp, vp, ctypes.c_int64, ci, vp, vp]
     L.iodf_codec_tables.restype = ci
     L.iodf_codec_tables.argtypes = [vp, vp]
+    L.iodf_tile_patches.restype = ci
+    L.iodf_tile_patches.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp]
+    L.iodf_untile_patches.restype = ci
+    L.iodf_untile_patches.argtypes = [vp, vp, ci, ci, vp, ci, ci, vp]
     _LIB = L
     return L
 
@@ -130,6 +134,16 @@ def iodf_encode(ctx, x_ptr, batch, words_ptr, cap_words, sizes_ptr, stream):
 
 def iodf_decode(ctx, words_ptr, cap_words, batch, x_ptr, stream):
     _check(load_library().iodf_decode(ctx, words_ptr, int(cap_words), int(batch), x_ptr, stream))
+
+
+def iodf_tile_patches(ctx, img_ptr, img_h, img_w, first_patch, n_patches, x_ptr, stream):
+    _check(load_library().iodf_tile_patches(ctx, img_ptr, int(img_h), int(img_w), int(first_patch), int(n_patches),
+                                            x_ptr, stream))
+
+
+def iodf_untile_patches(ctx, x_ptr, first_patch, n_patches, img_ptr, img_h, img_w, stream):
+    _check(load_library().iodf_untile_patches(ctx, x_ptr, int(first_patch), int(n_patches), img_ptr, int(img_h),
+                                              int(img_w), stream))
 
 
 def iodf_codec_tables():
@@ -245,6 +259,48 @@ class Flow:
         iodf_decode(self._ctx, ctypes.c_void_p(words.data_ptr()) if b else None, cap, b,
                     ctypes.c_void_p(x.data_ptr()) if b else None, self._stream())
         return x
+
+    def n_patches(self, img_h, img_w):
+        return -(-img_h // self.H) * -(-img_w // self.W)
+
+    def tile_patches(self, img, first=0, n=None, x=None):
+        """Planar image u8 [3,h,w] -> patches u8 [n,3,H,W] (row-major grid, 128 outside the image)."""
+        torch = self._torch
+        assert img.is_cuda and img.dtype == torch.uint8 and img.is_contiguous() and img.dim() == 3
+        _, h, w = img.shape
+        n = self.n_patches(h, w) - first if n is None else n
+        if x is None:
+            x = torch.empty((n, 3, self.H, self.W), dtype=torch.uint8, device=self.device)
+        iodf_tile_patches(self._ctx, ctypes.c_void_p(img.data_ptr()), h, w, first, n,
+                          ctypes.c_void_p(x.data_ptr()) if n else None, self._stream())
+        return x
+
+    def untile_patches(self, x, img, first=0):
+        torch = self._torch
+        assert x.is_cuda and x.dtype == torch.uint8 and x.is_contiguous()
+        assert img.is_cuda and img.dtype == torch.uint8 and img.is_contiguous() and img.dim() == 3
+        _, h, w = img.shape
+        iodf_untile_patches(self._ctx, ctypes.c_void_p(x.data_ptr()) if x.shape[0] else None, first, x.shape[0],
+                            ctypes.c_void_p(img.data_ptr()), h, w, self._stream())
+        return img
+
+    def encode_image(self, img):
+        """Whole image -> list of (containers, sizes) per sub-batch of at most max_batch patches."""
+        _, h, w = img.shape
+        total, out = self.n_patches(h, w), []
+        for first in range(0, total, self.max_batch):
+            n = min(self.max_batch, total - first)
+            out.append(self.encode(self.tile_patches(img, first, n)))
+        return out
+
+    def decode_image(self, parts, img_h, img_w):
+        torch = self._torch
+        img = torch.empty((3, img_h, img_w), dtype=torch.uint8, device=self.device)
+        first = 0
+        for words, _ in parts:
+            self.untile_patches(self.decode(words), img, first)
+            first += words.shape[0]
+        return img
 
     def codec_errors(self):
         """(clamped residuals, overflowing containers, broken lanes) since the last call; synchronises."""

@@ -22,6 +22,13 @@ hipError_t launch_factor_out(const int32_t* S, int B, int h, int w, int C, const
                              long long d, long long zoff, int32_t* Snext, hipStream_t st);
 hipError_t launch_unfactor(int32_t* S, int B, int h, int w, int C, const int32_t* phi, int c_keep, const int32_t* z,
                            long long d, long long zoff, const int32_t* Snext, hipStream_t st);
+// Patch-based coding of a large image (Sec. 5.2): planar img u8 [3][h][w] <-> patches
+// x u8 [n][3][H][W], patches first .. first+n-1 of the row-major grid of ceil(h/H) x ceil(w/W);
+// pixels outside the image read as 128 and are dropped on the way back.
+hipError_t launch_tile_patches(const uint8_t* img, int h, int w, int H, int W, int first, int n, uint8_t* x,
+                               hipStream_t st);
+hipError_t launch_untile_patches(const uint8_t* x, int first, int n, int H, int W, uint8_t* img, int h, int w,
+                                 hipStream_t st);
 // Zero `bytes` (multiple of 4) with a kernel (safe under stream capture).
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
 

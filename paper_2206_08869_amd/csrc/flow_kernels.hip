@@ -124,6 +124,37 @@ __global__ void k_unfactor(int32_t* __restrict__ S, int B, int h, int w, int C, 
     }
 }
 
+// Patch p (row-major over the grid of ceil(h/H) x ceil(w/W) patches) of a planar image
+// img[3][h][w]: x[p - first][c][y][x'] = img[c][py*H + y][px*W + x'], 128 outside the image.
+__global__ void k_tile_patches(const uint8_t* __restrict__ img, int h, int w, int H, int W, int first, int n,
+                               uint8_t* __restrict__ x) {
+    const int pw = (w + W - 1) / W;
+    const long long total = (long long)n * 3 * H * W;
+    for (long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x; t < total; t += (long long)gridDim.x * blockDim.x) {
+        const int xx = (int)(t % W);
+        const int yy = (int)((t / W) % H);
+        const int c = (int)((t / ((long long)W * H)) % 3);
+        const int p = first + (int)(t / ((long long)W * H * 3));
+        const int gy = (p / pw) * H + yy, gx = (p % pw) * W + xx;
+        x[t] = (gy < h && gx < w) ? img[((long long)c * h + gy) * w + gx] : (uint8_t)128;
+    }
+}
+
+// Inverse: pixels of the patches that fall inside the image are written back.
+__global__ void k_untile_patches(const uint8_t* __restrict__ x, int first, int n, int H, int W, uint8_t* __restrict__ img,
+                                 int h, int w) {
+    const int pw = (w + W - 1) / W;
+    const long long total = (long long)n * 3 * H * W;
+    for (long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x; t < total; t += (long long)gridDim.x * blockDim.x) {
+        const int xx = (int)(t % W);
+        const int yy = (int)((t / W) % H);
+        const int c = (int)((t / ((long long)W * H)) % 3);
+        const int p = first + (int)(t / ((long long)W * H * 3));
+        const int gy = (p / pw) * H + yy, gx = (p % pw) * W + xx;
+        if (gy < h && gx < w) img[((long long)c * h + gy) * w + gx] = x[t];
+    }
+}
+
 __global__ void k_fill_zero(unsigned* __restrict__ p, long long n_words) {
     for (long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x; t < n_words; t += (long long)gridDim.x * blockDim.x)
         p[t] = 0u;
@@ -173,6 +204,28 @@ hipError_t launch_unfactor(int32_t* S, int B, int h, int w, int C, const int32_t
     if (B <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_unfactor, dim3(grid_for((long long)B * C * h * w)), dim3(TPB), 0, st, S, B, h, w, C, phi,
                        c_keep, z, d, zoff, Snext);
+    return hipGetLastError();
+}
+
+hipError_t launch_tile_patches(const uint8_t* img, int h, int w, int H, int W, int first, int n, uint8_t* x,
+                               hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    if (h < 1 || w < 1 || H < 1 || W < 1 || first < 0 ||
+        (long long)first + n > (long long)((h + H - 1) / H) * ((w + W - 1) / W))
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_tile_patches, dim3(grid_for((long long)n * 3 * H * W)), dim3(TPB), 0, st, img, h, w, H, W, first,
+                       n, x);
+    return hipGetLastError();
+}
+
+hipError_t launch_untile_patches(const uint8_t* x, int first, int n, int H, int W, uint8_t* img, int h, int w,
+                                 hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    if (h < 1 || w < 1 || H < 1 || W < 1 || first < 0 ||
+        (long long)first + n > (long long)((h + H - 1) / H) * ((w + W - 1) / W))
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_untile_patches, dim3(grid_for((long long)n * 3 * H * W)), dim3(TPB), 0, st, x, first, n, H, W,
+                       img, h, w);
     return hipGetLastError();
 }
 

@@ -1098,6 +1098,34 @@ int iodf_decode(iodf_ctx* ctx, const uint32_t* words_dev, int64_t cap_words, int
     return IODF_OK;
 }
 
+int iodf_tile_patches(iodf_ctx* ctx, const uint8_t* img_dev, int img_h, int img_w, int first_patch, int n_patches,
+                      uint8_t* x_dev, void* stream) {
+    if (!ctx || img_h < 1 || img_w < 1 || first_patch < 0 || n_patches < 0) return IODF_E_ARG;
+    if (n_patches == 0) return IODF_OK;
+    if (!img_dev || !x_dev) return IODF_E_ARG;
+    const long long grid = (long long)((img_h + ctx->shape.H - 1) / ctx->shape.H) *
+                           ((img_w + ctx->shape.W - 1) / ctx->shape.W);
+    if ((long long)first_patch + n_patches > grid) return IODF_E_ARG;
+    HIP_TRY(hipSetDevice(ctx->device));
+    HIP_TRY(launch_tile_patches(img_dev, img_h, img_w, ctx->shape.H, ctx->shape.W, first_patch, n_patches, x_dev,
+                                (hipStream_t)stream));
+    return IODF_OK;
+}
+
+int iodf_untile_patches(iodf_ctx* ctx, const uint8_t* x_dev, int first_patch, int n_patches, uint8_t* img_dev,
+                        int img_h, int img_w, void* stream) {
+    if (!ctx || img_h < 1 || img_w < 1 || first_patch < 0 || n_patches < 0) return IODF_E_ARG;
+    if (n_patches == 0) return IODF_OK;
+    if (!img_dev || !x_dev) return IODF_E_ARG;
+    const long long grid = (long long)((img_h + ctx->shape.H - 1) / ctx->shape.H) *
+                           ((img_w + ctx->shape.W - 1) / ctx->shape.W);
+    if ((long long)first_patch + n_patches > grid) return IODF_E_ARG;
+    HIP_TRY(hipSetDevice(ctx->device));
+    HIP_TRY(launch_untile_patches(x_dev, first_patch, n_patches, ctx->shape.H, ctx->shape.W, img_dev, img_h, img_w,
+                                  (hipStream_t)stream));
+    return IODF_OK;
+}
+
 int iodf_profile_begin(iodf_ctx* ctx, int max_launches) {
     if (!ctx || max_launches < 1 || max_launches > (1 << 22)) return IODF_E_ARG;
     if (ctx->prof_on) return IODF_E_ARG;

@@ -44,3 +44,10 @@ def make_images(cfg, batch=None, seed=None, kind=None):
     g = g * 50.0 + 128.0
     g = np.sign(g) * np.floor(np.abs(g) + 0.5)
     return np.clip(g, 0, 255).astype(np.uint8)
+
+
+def make_large_image(h, w, seed=1900):
+    """One planar uint8 image [3, h, w] of the "filtered" kind, standing in for a high-resolution
+    photograph that is coded patch by patch."""
+    from types import SimpleNamespace
+    return make_images(SimpleNamespace(batch=1, seed_id=0, image_kind="filtered", H=h, W=w), batch=1, seed=seed)[0]

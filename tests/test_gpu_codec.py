@@ -174,3 +174,36 @@ def test_codec_with_and_without_graph_replay(monkeypatch):
     assert torch.equal(w_a, w_b) and torch.equal(s_a, s_b)
     assert torch.equal(flow.decode(w_b), xg)
     flow.close()
+
+
+def test_patch_based_coding_of_a_large_image():
+    import oracle
+    import torch
+    from synth import make_large_image
+    name = "mini_dense"           # 16 x 16 patches
+    flow = gpu_flow(name, max_batch=7)   # 30 patches in sub-batches of 7, 7, 7, 7, 2
+    h, w = 75, 90                 # ragged on both sides: 5 x 6 patches
+    img = make_large_image(h, w, seed=1901)
+    ig = to_gpu(img)
+    assert flow.n_patches(h, w) == 30
+    patches = flow.tile_patches(ig)
+    ref = oracle.tile_patches(img, 16, 16)
+    assert np.array_equal(patches.cpu().numpy(), ref)
+    sub = flow.tile_patches(ig, first=11, n=5)
+    assert np.array_equal(sub.cpu().numpy(), ref[11:16])
+    back = torch.zeros_like(ig)
+    flow.untile_patches(patches, back)
+    assert torch.equal(back, ig)
+    # whole image through the compressor, sub-batch by sub-batch; containers equal the oracle's
+    parts = flow.encode_image(ig)
+    assert [p[0].shape[0] for p in parts] == [7, 7, 7, 7, 2]
+    om = oracle_model(name)
+    ref_words, ref_sizes, _ = om.encode(ref)
+    got = np.concatenate([_u32(p[0]) for p in parts])
+    assert np.array_equal(got, ref_words) and np.array_equal(np.concatenate([_u32(p[1]) for p in parts]), ref_sizes)
+    img2 = flow.decode_image(parts, h, w)
+    assert torch.equal(img2, ig) and flow.codec_errors() == (0, 0, 0)
+    # patches beyond the grid are refused
+    with pytest.raises(iodf.IodfError):
+        flow.tile_patches(ig, first=28, n=3)
+    flow.close()

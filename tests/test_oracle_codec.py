@@ -341,3 +341,23 @@ def test_decoder_needs_the_heads():
     bad[0, sizes[0] - 1] ^= 0x4000
     x2, errs = om.decode(bad, x.shape[1:])
     assert errs > 0 or not np.array_equal(x, x2)
+
+
+# ---------------- patches ----------------
+
+def test_patch_tiling_against_a_reshape_and_by_hand():
+    rng = np.random.default_rng(3)
+    img = rng.integers(0, 256, size=(3, 8, 12), dtype=np.uint8)
+    p = oracle.tile_patches(img, 4, 4)
+    # exact multiple: the same thing written as a reshape
+    want = img.reshape(3, 2, 4, 3, 4).transpose(1, 3, 0, 2, 4).reshape(6, 3, 4, 4)
+    assert np.array_equal(p, want)
+    assert np.array_equal(oracle.untile_patches(p, 8, 12), img)
+    # ragged: 5 x 7 image, 4 x 4 patches -> 2 x 2 grid, mid-grey outside
+    img = np.arange(3 * 5 * 7, dtype=np.uint8).reshape(3, 5, 7)
+    p = oracle.tile_patches(img, 4, 4)
+    assert p.shape == (4, 3, 4, 4)
+    assert p[1, 0, 0, 2] == img[0, 0, 6] and p[1, 0, 0, 3] == 128          # patch (0,1): columns 4..7, 7 is outside
+    assert p[2, 2, 0, 1] == img[2, 4, 1] and np.all(p[2, :, 1:, :] == 128)  # patch (1,0): only row 4 is inside
+    assert p[3, 1, 0, 2] == img[1, 4, 6] and p[3, 1, 1, 2] == 128
+    assert np.array_equal(oracle.untile_patches(p, 5, 7), img)
