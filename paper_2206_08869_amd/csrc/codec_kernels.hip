@@ -12,8 +12,9 @@
 // the slot X mod M, finds the symbol whose [C, C + F) holds it by bisection over r, restores
 // X <- F * floor(X / M) + (X mod M) - C and pulls a word back in when X < 2^31.
 // A chunk's latents are dealt round-robin to 16 lanes, each an independent stream encoded
-// last-to-first. One thread runs one lane; the chains are serial, so these kernels are bound
-// by dependent integer latency, not by memory or the vector units.
+// last-to-first. The chains are serial (one thread per lane when encoding, sixteen when
+// decoding), so these kernels are bound by dependent integer latency, not by memory or the
+// vector units.
 #include "codec_kernels.h"
 
 #include <cmath>
@@ -191,21 +192,27 @@ __global__ __launch_bounds__(TPB) void k_rans_pack(const ChunkTable ct, const ui
     }
 }
 
-__global__ __launch_bounds__(64) void k_rans_decode_chunk(const CodecTables t, const ChunkTable ct, const int c,
-                                                          const uint32_t* __restrict__ cont, long long cap, int batch,
-                                                          const int8_t* __restrict__ codes, long long d_codes,
-                                                          int32_t* __restrict__ z, long long d,
-                                                          unsigned long long* errs) {
+// Sixteen threads serve one lane: each bisection round they test sixteen cut points of the current
+// interval at once (a ballot counts how many lie at or below the slot), so the 2^14 residuals are
+// isolated in four rounds (16 * 16 * 16 * 4) instead of fourteen. All sixteen keep the same coder
+// state; thread 0 of the group writes the latent. A workgroup of 256 threads holds the 16 lanes of
+// one image's chunk.
+__global__ __launch_bounds__(256) void k_rans_decode_chunk(const CodecTables t, const ChunkTable ct, const int c,
+                                                           const uint32_t* __restrict__ cont, long long cap, int batch,
+                                                           const int8_t* __restrict__ codes, long long d_codes,
+                                                           int32_t* __restrict__ z, long long d,
+                                                           unsigned long long* errs) {
     __shared__ int s_sig[kSigEntries];
     load_sig(s_sig, t.sig);
-    const long long tid = blockIdx.x * (long long)blockDim.x + threadIdx.x;
-    if (tid >= (long long)batch * kLanes) return;
-    const int b = (int)(tid / kLanes), j = (int)(tid % kLanes);
+    const int b = blockIdx.x;  // grid = batch
+    const int j = threadIdx.x >> 4, helper = threadIdx.x & 15;
+    const int grp_shift = (threadIdx.x & 63) & ~15;  // this group's first bit in the wave's ballot
     const int nslots = ct.n_chunks * kLanes;
     const long long header = 1 + 3LL * nslots;  // the host has checked cap >= header
     const uint32_t* cb = cont + (long long)b * cap;
     const int n = ct.n[c];
     const int k = j < n ? (n - j + kLanes - 1) / kLanes : 0;
+    const int kmax = (n + kLanes - 1) / kLanes;  // the same for every thread: ballots stay convergent
     int32_t* zc = z + (long long)b * d + ct.z_off[c];
     const int8_t* ci = codes ? codes + (long long)b * d_codes : nullptr;
     const long long total = cb[0];
@@ -219,30 +226,37 @@ __global__ __launch_bounds__(64) void k_rans_decode_chunk(const CodecTables t, c
     long long used = 0;
     unsigned long long X = (unsigned long long)cb[1 + nslots + 2 * slot] |
                            ((unsigned long long)cb[1 + nslots + 2 * slot + 1] << 32);
-    for (int p = 0; p < k; ++p) {
-        const int e = p * kLanes + j;
-        int m, l;
-        codes_of(ct, c, ci, e, m, l);
+    for (int p = 0; p < kmax; ++p) {
+        const bool active = p < k;
+        const int e = active ? p * kLanes + j : 0;
+        int m = kDefaultM, l = kDefaultL;
+        if (active) codes_of(ct, c, ci, e, m, l);
         const long long inv = t.inv[l + 128];
         const int v = (int)(X & (unsigned long long)(kMass - 1));
-        // G(-8192) = 0 <= v < M = G(8192): fourteen halvings isolate the symbol
-        int lo = -kAlphaR, hi = kAlphaR;
-#pragma unroll 1
-        for (int it = 0; it < 14; ++it) {
-            const int mid = (lo + hi) >> 1;
-            if (cdf(s_sig, mid, inv) <= v) lo = mid; else hi = mid;
+        // G(-8192) = 0 <= v < M = G(8192); cut points lo + (helper + 1) * step, the last one of the
+        // first three rounds is the interval's end (known to lie above the slot)
+        int lo = -kAlphaR;
+#pragma unroll
+        for (int round = 0; round < 4; ++round) {
+            const int step = round == 0 ? 1024 : round == 1 ? 64 : round == 2 ? 4 : 1;
+            const int cut = lo + (helper + 1) * step;
+            const bool below = (step == 1 ? helper < 3 : helper < 15) && cdf(s_sig, cut, inv) <= v;
+            const unsigned long long mask = __ballot(below);
+            lo += __popc((unsigned)(mask >> grp_shift) & 0xffffu) * step;
         }
         const int C = cdf(s_sig, lo, inv);
         const int F = cdf(s_sig, lo + 1, inv) - C;
-        zc[e] = lo + 2 * m;
-        X = (unsigned long long)F * (X >> kMassBits) + (unsigned long long)(v - C);
-        if (X < kStateLow) {
-            if (used < nw) X = (X << 32) | w[used++];
-            else { X <<= 32; bad = true; }
+        if (active) {
+            if (helper == 0) zc[e] = lo + 2 * m;
+            X = (unsigned long long)F * (X >> kMassBits) + (unsigned long long)(v - C);
+            if (X < kStateLow) {
+                if (used < nw) X = (X << 32) | w[used++];
+                else { X <<= 32; bad = true; }
+            }
         }
     }
     if (X != kStateLow || used != nw) bad = true;
-    if (bad) atomicAdd(errs + 2, 1ULL);
+    if (bad && helper == 0) atomicAdd(errs + 2, 1ULL);
 }
 
 int grid_for(long long n, int tpb) {
@@ -294,9 +308,8 @@ hipError_t launch_rans_decode_chunk(const CodecTables& t, const ChunkTable& ct, 
     if (!table_ok(ct) || c < 0 || c >= ct.n_chunks || !cont || !z || !errs || !t.sig || !t.inv ||
         cap < 1 + 3LL * ct.n_chunks * kLanes)
         return hipErrorInvalidValue;
-    const long long threads = (long long)batch * kLanes;
-    hipLaunchKernelGGL(k_rans_decode_chunk, dim3((unsigned)((threads + 63) / 64)), dim3(64), 0, st, t, ct, c, cont, cap,
-                       batch, codes, d_codes, z, d, errs);
+    hipLaunchKernelGGL(k_rans_decode_chunk, dim3(batch), dim3(256), 0, st, t, ct, c, cont, cap, batch, codes, d_codes, z,
+                       d, errs);
     return hipGetLastError();
 }
 
