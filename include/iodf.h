@@ -8,7 +8,9 @@
  * half of the channels out. t() is an integer-only network: 8-bit codes, int8 x
  * int8 convolutions with 32-bit accumulator and bias, a per-channel fixed-point
  * rescale back to 8 bit, integer ReLU (Sec. 4.1, Eq. 2-5), with gated-off filters
- * physically removed and residual sums done by scatter-add (Sec. 4.4, Eq. 8).
+ * and the matching input columns of their consumers physically removed (Sec. 4.4,
+ * Eq. 8); where a residual shortcut needs the unpruned width, a gated-off filter is
+ * kept as an all-zero row, which adds exactly the 0 that its removal would.
  *
  * Pointer conventions: "host" = ordinary process memory; "device" = memory of
  * the GPU the context was created on, owned by the caller (for instance a

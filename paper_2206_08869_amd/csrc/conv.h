@@ -61,14 +61,13 @@ struct ConvArgs {
     const int32_t* clamp_hi;
     int log2_w, log2_hw;  // filled by launch_conv: log2 of w and of h*w when both are powers of two, else -1
     int32_t* partial;  // optional split-K scratch: int32 [npix][n_pad], all zero between launches
-    int n_store;   // channels written (<= n_pad); multiple of 4 in MODE_ACT without out_map
+    int n_store;   // channels written (<= n_pad); multiple of 4 in MODE_ACT
     int mode;
     int relu;
     // MODE_ACT
     int8_t* out;
     long long out_plane;
     int out_chunk0;
-    const int32_t* out_map;  // optional: output channel n is stored at channel out_map[n] (scatter-add)
     int shortcut;            // add the 8-bit code already stored at the output location
     // MODE_COUPLE
     int32_t* state;          // int32 pixel-major [npix][state_c]

@@ -81,7 +81,7 @@ __device__ __forceinline__ int rq_fast_abs(unsigned ua, int M, int sh) {
     return (int)((__umulhi(ua, (unsigned)M) + (1u << (sh - 1))) >> sh);
 }
 
-// Epilogue for plain 8-bit pixel-major stores (MODE_ACT, no scatter map, every shift >= 33,
+// Epilogue for plain 8-bit pixel-major stores (MODE_ACT, every shift >= 33,
 // n_store a multiple of 16). After the requantise each lane holds four dwords of 4 channels
 // (register quads g = 0..3: channels g*8 + half*4 ..); three rounds of v_permlane32_swap
 // between the two wave halves regroup them into 16 consecutive channels per lane, stored
@@ -214,7 +214,7 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs& a, v16i (&acc)[TC]
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         if (nb + e >= a.n_store) continue;
-                        const int ch = a.out_map ? a.out_map[nb + e] : nb + e;
+                        const int ch = nb + e;
                         const int bi = m / hw, qi = m - bi * hw, ii = qi / a.w, ji = qi - ii * a.w;
                         const long long pp = (long long)bi * ((a.h + 2) * (a.w + 2)) + (ii + 1) * (a.w + 2) + (ji + 1);
                         int8_t* o = a.out + (long long)(a.out_chunk0 + (ch >> 6)) * a.out_plane + pp * 64 + (ch & 63);
@@ -511,7 +511,7 @@ __global__ void conv_splitk_finish(const ConvArgs a) {
         *ps = 0;
         int y = rq_dev(av, a.mul[c], a.shift[c] + (a.rq_fast ? 32 : 0));
         if (a.mode == MODE_ACT) {
-            const int ch = a.out_map ? a.out_map[c] : c;
+            const int ch = c;
             const int bi = m / hw, qi = m - bi * hw, ii = qi / a.w, ji = qi - ii * a.w;
             const long long pp = (long long)bi * ((a.h + 2) * (a.w + 2)) + (ii + 1) * (a.w + 2) + (ji + 1);
             int8_t* o = a.out + (long long)(a.out_chunk0 + (ch >> 6)) * a.out_plane + pp * 64 + (ch & 63);
@@ -616,7 +616,7 @@ int conv_pick_tile(const ConvArgs& a) {
 // supports it, and only when the caller supplied the scratch).
 int conv_pick_splits(const ConvArgs& a, int tile) {
     if (a.mode == MODE_RAW) return 1;  // its scratch is written, not accumulated
-    const bool fast = a.mode == MODE_ACT && !a.out_map && a.rq_fast && a.n_store % 16 == 0;
+    const bool fast = a.mode == MODE_ACT && a.rq_fast && a.n_store % 16 == 0;
     if (fast || !a.partial || tile < 0) return 1;
     const TileCfg& t = kTiles[tile];
     const long long blocks = (long long)((a.npix + t.bp - 1) / t.bp) * ((a.n_store + t.bc - 1) / t.bc);
@@ -640,7 +640,7 @@ hipError_t launch_conv(const ConvArgs& a_in, hipStream_t stream) {
     const TileCfg& t = kTiles[best];
     const int npb = (a.npix + t.bp - 1) / t.bp, ncb = a.n_pad / t.bc;
     const int grid = ((npb + 7) / 8) * 8 * ncb;
-    const bool fast = a.mode == MODE_ACT && !a.out_map && a.rq_fast && a.n_store % 16 == 0;
+    const bool fast = a.mode == MODE_ACT && a.rq_fast && a.n_store % 16 == 0;
     const int epi = !fast ? EPI_ANY : (a.relu && !a.shortcut && a.clamp_hi) ? EPI_FAST_RELU : EPI_FAST;
     const int splits = conv_pick_splits(a, best);
     hipLaunchKernelGGL(t.kern[epi], dim3(grid, splits), dim3(t.threads), t.lds, stream, a, npb, ncb);

@@ -195,7 +195,6 @@ struct DevLayer {
     int out_buf, out_off;  // output tensor (MODE_ACT)
     size_t wgt_off, bias_off, mul_off, shift_off;  // byte offsets into the parameter arena
     size_t hi_off = (size_t)-1;                    // rq_fast layers: clamp bound per channel
-    size_t map_off;                                // (size_t)-1 when there is no scatter map
     // tap-expanded 3x3 last layer (see TapSumArgs): the GEMM is 1x1 with 9 * c_out rows and
     // stores raw accumulators; these are the constants of the summing pass
     int expand_c_out = 0, final_mode = 0;
@@ -210,8 +209,6 @@ struct DevNet {
     int kind, level, C, C_in, C_out, cin_pad0;
     int32_t M_in;
     int s_in;
-    bool zero_a;        // clear BUF_A before conv_in (scatter-written residual stream)
-    int a_stride;       // row width of BUF_A for this network (what zero_a clears)
     size_t phi_off;     // byte offset of this coupling's composed index map (int32[C]); heads: the level's last
     std::vector<DevLayer> layers;
 };
@@ -255,7 +252,6 @@ void pack_layer(Arena& A, const HostLayer& L, const std::vector<int>& rows, cons
     D.n_pad = round64((int)rows.size());
     D.relu = L.relu;
     D.shortcut = L.shortcut;
-    D.map_off = (size_t)-1;
     const size_t wbytes = (size_t)D.n_pad * taps * cin_pad;
     D.wgt_off = A.alloc(wbytes);
     D.bias_off = A.alloc(4 * (size_t)D.n_pad);
@@ -324,7 +320,6 @@ void pack_last_expanded(Arena& A, const HostLayer& L, const std::vector<int>& co
     D.n_store = rows;
     D.relu = L.relu;
     D.shortcut = 0;
-    D.map_off = (size_t)-1;
     D.rq_fast = 0;
     D.mode = MODE_RAW;
     D.expand_c_out = co;
@@ -357,13 +352,6 @@ void pack_last_expanded(Arena& A, const HostLayer& L, const std::vector<int>& co
     D.wide = false;
 }
 
-size_t put_map(Arena& A, const std::vector<int>& rows, int n_pad) {
-    const size_t off = A.alloc(4 * (size_t)n_pad);
-    int32_t* m = (int32_t*)(A.host.data() + off);
-    for (size_t n = 0; n < rows.size(); ++n) m[n] = rows[n];
-    return off;
-}
-
 std::vector<int> identity_map(int n) {
     std::vector<int> v(n);
     for (int i = 0; i < n; ++i) v[i] = i;
@@ -377,7 +365,6 @@ void plan_net(Arena& A, const HostModel& m, const HostNet& N, DevNet& D, int buf
     D.kind = N.kind; D.level = N.level; D.C = N.C; D.C_in = N.C_in; D.C_out = N.C_out;
     D.M_in = N.M_in; D.s_in = N.s_in;
     D.cin_pad0 = round64(N.C_in);
-    D.zero_a = false;
     D.layers.resize(nl);
     buf_w[BUF_XQ] = std::max(buf_w[BUF_XQ], D.cin_pad0);
     const int last_mode = N.kind == 0 ? MODE_COUPLE : MODE_CODES;
@@ -404,13 +391,11 @@ void plan_net(Arena& A, const HostModel& m, const HostNet& N, DevNet& D, int buf
         D.layers[0].n_store = fw;
         plan_last(L[1], rank_map(L[0], 0), fw, D.layers[1]);
         D.layers[1].in_buf = BUF_A; D.layers[1].in_off = 0; D.layers[1].out_buf = -1; D.layers[1].out_off = 0;
-        D.a_stride = fw;
         buf_w[BUF_A] = std::max(buf_w[BUF_A], fw);
     } else if (m.family == FAM_RESNET) {
         // BUF_A: residual stream at full width; BUF_B: block-internal feature (compacted)
         const int Wd = L[0].C_out;
         const int rw = round64(Wd);
-        D.a_stride = rw;
         buf_w[BUF_A] = std::max(buf_w[BUF_A], rw);
         // The stream keeps its full width (the shortcut adds into unpruned channels, Sec. 4.4), so
         // the layers that write it keep gated-off filters as zero rows: a zero row adds 0 to the
@@ -421,8 +406,7 @@ void plan_net(Arena& A, const HostModel& m, const HostNet& N, DevNet& D, int buf
             pack_layer(A, L[0], all_rows, identity_map(N.C_in), D.cin_pad0, D.layers[0], true);
             io(D.layers[0], BUF_XQ, 0, D.cin_pad0, BUF_A, 0, rw, MODE_ACT);
             D.layers[0].n_store = rw;
-            D.zero_a = false;
-        }
+                }
         for (int l = 1; l + 1 < nl; l += 2) {
             const std::vector<int> r1 = kept_rows(L[l]);
             const int tw = round64((int)r1.size());
@@ -450,7 +434,6 @@ void plan_net(Arena& A, const HostModel& m, const HostNet& N, DevNet& D, int buf
             blk_off[j + 1] = blk_off[j] + round64((int)kept_rows(P).size());
         }
         const int cw = blk_off[depth + 1];
-        D.a_stride = cw;
         buf_w[BUF_A] = std::max(buf_w[BUF_A], cw);
         pack_layer(A, L[0], kept_rows(L[0]), identity_map(N.C_in), D.cin_pad0, D.layers[0]);
         io(D.layers[0], BUF_XQ, 0, D.cin_pad0, BUF_A, 0, cw, MODE_ACT);
@@ -565,9 +548,6 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
     PROF_LAUNCH(ctx, st, CLS_QUANT_IN, 0, (long long)npix * (4 * N.C_in + N.cin_pad0),
                 launch_quant_in(ctx->state[lv], npix, h, w, N.C, phi, N.C_in, N.M_in, N.s_in, ctx->buf[lv][BUF_XQ],
                                 N.cin_pad0, plane, st));
-    if (N.zero_a)  // whole planes of the residual stream; zeroing borders again is harmless
-        PROF_LAUNCH(ctx, st, CLS_FILL_ZERO, 0, (long long)npix * N.a_stride,
-                    launch_fill_zero(ctx->buf[lv][BUF_A], (size_t)plane * (N.a_stride / 64), st));
     for (const DevLayer& L : N.layers) {
         ConvArgs a;
         memset(&a, 0, sizeof(a));
@@ -592,7 +572,6 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
             a.out = ctx->buf[lv][L.out_buf];
             a.out_plane = plane;
             a.out_chunk0 = L.out_off / 64;
-            a.out_map = L.map_off == (size_t)-1 ? nullptr : (const int32_t*)(ctx->params + L.map_off);
             a.shortcut = L.shortcut;
         } else if (L.mode == MODE_COUPLE) {
             a.state = ctx->state[lv];
