@@ -225,6 +225,18 @@ def main():
                                      compressed_bytes=int(comp),
                                      round_trip_exact=bool(torch.equal(back, big)) and flow.codec_errors() == (0, 0, 0))
 
+    # what a plain device-to-device copy sustains on this machine (reference for the bandwidth-bound passes)
+    src = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(10):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    copy_gbs = 10 * 2.0 * src.numel() / (time.perf_counter() - t1) / 1e9
+    del src, dst
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -264,6 +276,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,
+        "hbm_copy_gbs": round(copy_gbs, 1),
         "setup_s": {"generate": round(t_gen, 1), "init": round(t_init, 1)},
     }
     print(json.dumps(out))
