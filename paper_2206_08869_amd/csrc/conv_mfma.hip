@@ -595,11 +595,12 @@ hipError_t conv_setup() {
 int conv_num_tiles() { return kNumTiles; }
 const char* conv_tile_name(int tile) { return tile >= 0 && tile < kNumTiles ? kTiles[tile].name : "?"; }
 
-// Largest tile that still fills the chip; otherwise the valid tile with most workgroups.
+// First tile in table order that still fills the chip; otherwise the valid tile with most
+// workgroups, and among equals the one that multiplies the least padding.
 int conv_pick_tile(const ConvArgs& a) {
     if (!args_ok(a)) return -1;
     int best = -1;
-    long long best_blocks = -1;
+    long long best_blocks = -1, best_work = 0;
     const int forced = forced_tile();
     if (forced >= 0 && forced < kNumTiles && a.n_pad % kTiles[forced].bc == 0) return forced;
     for (int i = 0; i < kNumTiles; ++i) {
@@ -607,7 +608,12 @@ int conv_pick_tile(const ConvArgs& a) {
         const long long blocks = (long long)((a.npix + kTiles[i].bp - 1) / kTiles[i].bp) *
                                  ((a.n_store + kTiles[i].bc - 1) / kTiles[i].bc);
         if (blocks >= 256) return i;
-        if (blocks > best_blocks) { best_blocks = blocks; best = i; }
+        const long long work = blocks * kTiles[i].bc * kTiles[i].bp;
+        if (blocks > best_blocks || (blocks == best_blocks && work < best_work)) {
+            best_blocks = blocks;
+            best_work = work;
+            best = i;
+        }
     }
     return best;
 }
