@@ -145,11 +145,13 @@ def main():
             if s["macs"]:
                 k["tops"] = round(2.0 * s["macs"] / (s["total_ms"] * 1e-3) / 1e12, 2)
                 k["frac_of_int8_peak"] = round(k["tops"] / INT8_PEAK_TOPS, 4)
+                if s["issued_macs"]:   # share of the matrix-core work that is not tile or channel padding
+                    k["algorithmic_over_issued"] = round(s["macs"] / s["issued_macs"], 4)
             k["alg_gbs"] = round(s["bytes"] / (s["total_ms"] * 1e-3) / 1e9, 1)
             kernels.append(k)
             base = s["name"].rsplit(" ", 1)[0] if s["name"].endswith(("3x3", "1x1")) else s["name"]
-            agg = per_kernel.setdefault(base, dict(name=base, launches=0, total_ms=0.0, macs=0, bytes=0))
-            for f in ("launches", "total_ms", "macs", "bytes"):
+            agg = per_kernel.setdefault(base, dict(name=base, launches=0, total_ms=0.0, macs=0, bytes=0, issued_macs=0))
+            for f in ("launches", "total_ms", "macs", "bytes", "issued_macs"):
                 agg[f] += s[f]
         dom = max((s for s in per_kernel.values() if s["macs"]), key=lambda s: s["total_ms"])
         achieved = 2.0 * dom["macs"] / (dom["total_ms"] * 1e-3) / 1e12
@@ -158,6 +160,7 @@ def main():
                         traffic=PMC_TRAFFIC_BYTES.get((cfg.name, batch, dom["name"])),
                         algorithmic_bytes_per_launch=round(dom["bytes"] / dom["launches"]),
                         algorithmic_ops_per_launch=round(2.0 * dom["macs"] / dom["launches"]),
+                        issued_ops_per_launch=round(2.0 * dom["issued_macs"] / dom["launches"]),
                         launches=dom["launches"], avg_launch_ms=round(dom["total_ms"] / dom["launches"], 5),
                         share_of_step=round(dom["total_ms"] / (1e3 * elapsed), 4),
                         instrumented_ms_per_step=round(1e3 * prof_elapsed / args.steps, 3))

@@ -174,6 +174,7 @@ typedef struct iodf_kernel_stat {
     double total_ms;    /* sum of event-measured durations */
     int64_t macs;       /* algorithmic multiply-accumulates of those launches (kept channels, true widths) */
     int64_t bytes;      /* algorithmic bytes: live inputs + outputs (+ weights) read or written once */
+    int64_t issued_macs; /* multiply-accumulates the matrix cores ran: whole tiles at padded widths (0: not a conv) */
 } iodf_kernel_stat;
 int iodf_profile_begin(iodf_ctx* ctx, int max_launches);
 int iodf_profile_end(iodf_ctx* ctx, iodf_kernel_stat* stats, int max_stats, int* n_stats);

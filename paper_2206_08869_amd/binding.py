@@ -28,7 +28,7 @@ EXPORTS = ["iodf_init", "iodf_forward", "iodf_inverse", "iodf_query", "iodf_free
 
 class KernelStat(ctypes.Structure):
     _fields_ = [("name", ctypes.c_char * 48), ("launches", ctypes.c_int64), ("total_ms", ctypes.c_double),
-                ("macs", ctypes.c_int64), ("bytes", ctypes.c_int64)]
+                ("macs", ctypes.c_int64), ("bytes", ctypes.c_int64), ("issued_macs", ctypes.c_int64)]
 
 
 class IodfError(RuntimeError):
@@ -170,7 +170,8 @@ def iodf_profile_end(ctx):
     n = ctypes.c_int(0)
     _check(load_library().iodf_profile_end(ctx, arr, 32, ctypes.byref(n)))
     return [dict(name=arr[i].name.decode(), launches=int(arr[i].launches), total_ms=float(arr[i].total_ms),
-                 macs=int(arr[i].macs), bytes=int(arr[i].bytes)) for i in range(n.value)]
+                 macs=int(arr[i].macs), bytes=int(arr[i].bytes), issued_macs=int(arr[i].issued_macs))
+            for i in range(n.value)]
 
 
 def iodf_free(ctx):

@@ -87,6 +87,8 @@ hipError_t launch_conv(const ConvArgs& a, hipStream_t stream);
 int conv_pick_tile(const ConvArgs& a);
 int conv_num_tiles();
 const char* conv_tile_name(int tile);
+// Channels x pixels of a tile (0, 0 for an invalid index).
+void conv_tile_dims(int tile, int* bc, int* bp);
 // One-time per-process set-up of kernel attributes (dynamic LDS sizes).
 hipError_t conv_setup();
 

@@ -594,6 +594,11 @@ hipError_t conv_setup() {
 
 int conv_num_tiles() { return kNumTiles; }
 const char* conv_tile_name(int tile) { return tile >= 0 && tile < kNumTiles ? kTiles[tile].name : "?"; }
+void conv_tile_dims(int tile, int* bc, int* bp) {
+    const bool ok = tile >= 0 && tile < kNumTiles;
+    *bc = ok ? kTiles[tile].bc : 0;
+    *bp = ok ? kTiles[tile].bp : 0;
+}
 
 // First tile in table order that still fills the chip; otherwise the valid tile with most
 // workgroups, and among equals the one that multiplies the least padding.

@@ -504,7 +504,7 @@ struct iodf_ctx {
     uint32_t* lane_meta = nullptr;     // [max_batch][n_chunks * 16][4]
     unsigned long long* codec_errs = nullptr;  // [3]: clamped residuals, overflowing containers, broken lanes
     // optional per-launch timing (iodf_profile_begin / iodf_profile_end)
-    struct ProfRec { int cls; long long macs, bytes; };
+    struct ProfRec { int cls; long long macs, bytes, issued; };
     bool prof_on = false;
     std::vector<hipEvent_t> prof_ev;
     std::vector<ProfRec> prof_recs;
@@ -523,9 +523,18 @@ bool prof_start(iodf_ctx* ctx, hipStream_t st) {
     return hipEventRecord(ctx->prof_ev[2 * ctx->prof_recs.size()], st) == hipSuccess;
 }
 
-void prof_stop(iodf_ctx* ctx, hipStream_t st, int cls, long long macs, long long bytes) {
+void prof_stop(iodf_ctx* ctx, hipStream_t st, int cls, long long macs, long long bytes, long long issued = 0) {
     (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_recs.size() + 1], st);
-    ctx->prof_recs.push_back({cls, macs, bytes});
+    ctx->prof_recs.push_back({cls, macs, bytes, issued});
+}
+
+// Multiply-accumulates the matrix cores actually run for a conv launch: whole tiles, padded widths.
+long long issued_macs(const ConvArgs& a) {
+    int bc = 0, bp = 0;
+    conv_tile_dims(conv_pick_tile(a), &bc, &bp);
+    if (!bc) return 0;
+    const long long px = (long long)((a.npix + bp - 1) / bp) * bp, ch = (long long)((a.n_store + bc - 1) / bc) * bc;
+    return px * ch * a.cin_pad * a.taps;
 }
 
 // Launch through `call`, bracketed by events when profiling is on.
@@ -587,8 +596,13 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
         }
         const int fmode = L.mode == MODE_RAW ? L.final_mode : L.mode;
         const long long extra = fmode == MODE_COUPLE ? 8LL * N.C_out : 0;  // state read + write
-        PROF_LAUNCH(ctx, st, NUM_FLOW_CLS + 2 * conv_pick_tile(a) + (a.taps == 9), L.macs_per_pixel * npix,
-                    (L.bytes_per_pixel + extra) * npix + L.wgt_bytes, launch_conv(a, st));
+        {
+            const bool p__ = prof_start(ctx, st);
+            HIP_TRY(launch_conv(a, st));
+            if (p__)
+                prof_stop(ctx, st, NUM_FLOW_CLS + 2 * conv_pick_tile(a) + (a.taps == 9), L.macs_per_pixel * npix,
+                          (L.bytes_per_pixel + extra) * npix + L.wgt_bytes, issued_macs(a));
+        }
         if (L.mode == MODE_RAW) {
             TapSumArgs t;
             memset(&t, 0, sizeof(t));
@@ -1152,6 +1166,7 @@ int iodf_profile_end(iodf_ctx* ctx, iodf_kernel_stat* stats, int max_stats, int*
         acc[r.cls].launches += 1;
         acc[r.cls].total_ms += ms;
         acc[r.cls].macs += r.macs;
+        acc[r.cls].issued_macs += r.issued;
         acc[r.cls].bytes += r.bytes;
     }
     for (hipEvent_t& e : ctx->prof_ev)
