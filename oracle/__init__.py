@@ -41,6 +41,10 @@ def lib():
         L.orc_conv_acc.argtypes = [vp, ci, ci, ci, vp, ci, ci, vp, vp, vp]
         L.orc_epilogue.restype = None
         L.orc_epilogue.argtypes = [vp, ci, ci, vp, vp, vp, ci, vp, vp]
+        L.orc_conv_acc_u8.restype = None
+        L.orc_conv_acc_u8.argtypes = [vp, ci, ci, ci, vp, ci, ci, vp, vp, vp]
+        L.orc_epilogue_u8.restype = None
+        L.orc_epilogue_u8.argtypes = [vp, ci, ci, vp, vp, vp, vp, vp]
         L.orc_squeeze.restype = None
         L.orc_squeeze.argtypes = [vp, ci, ci, ci, vp]
         L.orc_unsqueeze.restype = None
@@ -123,6 +127,34 @@ def conv_acc(x, W, bias=None, gate=None):
     acc = np.zeros((C, h, w), dtype=np.int32)
     lib().orc_conv_acc(_p(x), D, h, w, _p(W), C, k, _p(bias), _p(gate), _p(acc))
     return acc
+
+
+def conv_acc_u8(x, W, bias=None, gate=None):
+    """As conv_acc with x uint8 [D,h,w] read as unsigned codes."""
+    x = np.ascontiguousarray(x, dtype=np.uint8)
+    W = np.ascontiguousarray(W, dtype=np.int8)
+    D, h, w = x.shape
+    C, D2, k, k2 = W.shape
+    assert D == D2 and k == k2
+    bias = None if bias is None else np.ascontiguousarray(bias, dtype=np.int32)
+    gate = None if gate is None else np.ascontiguousarray(gate, dtype=np.uint8)
+    acc = np.zeros((C, h, w), dtype=np.int32)
+    lib().orc_conv_acc_u8(_p(x), D, h, w, _p(W), C, k, _p(bias), _p(gate), _p(acc))
+    return acc
+
+
+def epilogue_u8(acc, M, shift, gate=None, shortcut=None):
+    """Unsigned-format epilogue (always with ReLU): uint8 codes saturated to [0, 255]."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    C = acc.shape[0]
+    hw = int(np.prod(acc.shape[1:]))
+    M = np.ascontiguousarray(M, dtype=np.int32)
+    shift = np.ascontiguousarray(shift, dtype=np.uint8)
+    gate = None if gate is None else np.ascontiguousarray(gate, dtype=np.uint8)
+    shortcut = None if shortcut is None else np.ascontiguousarray(shortcut, dtype=np.uint8)
+    y = np.zeros(acc.shape, dtype=np.uint8)
+    lib().orc_epilogue_u8(_p(acc), C, hw, _p(M), _p(shift), _p(gate), _p(shortcut), _p(y))
+    return y
 
 
 def epilogue(acc, M, shift, gate=None, relu=False, shortcut=None):

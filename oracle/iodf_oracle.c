@@ -32,6 +32,7 @@ typedef struct {
 struct orc_model {
     uint8_t* blob;
     int H, W, levels, couplings, family, width, depth, has_heads, n_nets;
+    int act_unsigned; /* tensors that leave a ReLU hold unsigned codes 0..255 (Eq. 3) */
     orc_net* nets;
 };
 
@@ -59,8 +60,11 @@ int32_t orc_sat8(int64_t u) {
     return (int32_t)u;
 }
 
-void orc_conv_acc(const int8_t* x, int D, int h, int w, const int8_t* W, int C, int k,
-                  const int32_t* bias, const uint8_t* gate, int32_t* acc) {
+/* Eq. 4 with the input codes read as signed (-128..127) or, for xu != 0, as unsigned
+ * (0..255) bytes (Eq. 3: activations after a ReLU may use the unsigned format). */
+static void conv_acc_any(const void* xv, int xu, int D, int h, int w, const int8_t* W, int C, int k,
+                         const int32_t* bias, const uint8_t* gate, int32_t* acc) {
+    const int8_t* x = (const int8_t*)xv;
     const int p = (k - 1) / 2;
     const int nt = orc_get_threads();
 #pragma omp parallel for num_threads(nt) schedule(static)
@@ -80,7 +84,10 @@ void orc_conv_acc(const int8_t* x, int D, int h, int w, const int8_t* W, int C, 
                     for (int i = i0; i < i1; ++i) {
                         int32_t* ar = a + i * w;
                         const int8_t* xr = xc + (i + ky - p) * w + (kx - p);
-                        for (int j = j0; j < j1; ++j) ar[j] += wv * (int32_t)xr[j];
+                        if (xu)
+                            for (int j = j0; j < j1; ++j) ar[j] += wv * (int32_t)(uint8_t)xr[j];
+                        else
+                            for (int j = j0; j < j1; ++j) ar[j] += wv * (int32_t)xr[j];
                     }
                 }
             }
@@ -88,8 +95,20 @@ void orc_conv_acc(const int8_t* x, int D, int h, int w, const int8_t* W, int C, 
     }
 }
 
-void orc_epilogue(const int32_t* acc, int C, int hw, const int32_t* M, const uint8_t* shift,
-                  const uint8_t* gate, int relu, const int8_t* shortcut, int8_t* y) {
+void orc_conv_acc(const int8_t* x, int D, int h, int w, const int8_t* W, int C, int k,
+                  const int32_t* bias, const uint8_t* gate, int32_t* acc) {
+    conv_acc_any(x, 0, D, h, w, W, C, k, bias, gate, acc);
+}
+
+void orc_conv_acc_u8(const uint8_t* x, int D, int h, int w, const int8_t* W, int C, int k,
+                     const int32_t* bias, const uint8_t* gate, int32_t* acc) {
+    conv_acc_any(x, 1, D, h, w, W, C, k, bias, gate, acc);
+}
+
+/* su: the shortcut bytes are unsigned codes; yu: the output is stored as unsigned codes,
+ * saturated to [0, 255] (only meaningful after a ReLU). */
+static void epilogue_any(const int32_t* acc, int C, int hw, const int32_t* M, const uint8_t* shift,
+                         const uint8_t* gate, int relu, const void* shortcut, int su, void* y, int yu) {
     for (int c = 0; c < C; ++c) {
         for (int i = 0; i < hw; ++i) {
             const size_t o = (size_t)c * hw + i;
@@ -97,11 +116,22 @@ void orc_epilogue(const int32_t* acc, int C, int hw, const int32_t* M, const uin
             int64_t u = (gate && !gate[c]) ? 0 : orc_rq(acc[o], M[c], shift[c]);
             /* the shortcut adds the block input's 8-bit code in the wide integer;
              * it is full width, so this is the scatter-add of Sec. 4.4 */
-            if (shortcut) u += shortcut[o];
+            if (shortcut) u += su ? (int64_t)((const uint8_t*)shortcut)[o] : (int64_t)((const int8_t*)shortcut)[o];
             if (relu && u < 0) u = 0;
-            y[o] = (int8_t)orc_sat8(u);
+            if (yu) ((uint8_t*)y)[o] = (uint8_t)(u > 255 ? 255 : (u < 0 ? 0 : u));
+            else ((int8_t*)y)[o] = (int8_t)orc_sat8(u);
         }
     }
+}
+
+void orc_epilogue(const int32_t* acc, int C, int hw, const int32_t* M, const uint8_t* shift,
+                  const uint8_t* gate, int relu, const int8_t* shortcut, int8_t* y) {
+    epilogue_any(acc, C, hw, M, shift, gate, relu, shortcut, 0, y, 0);
+}
+
+void orc_epilogue_u8(const int32_t* acc, int C, int hw, const int32_t* M, const uint8_t* shift,
+                     const uint8_t* gate, const uint8_t* shortcut, uint8_t* y) {
+    epilogue_any(acc, C, hw, M, shift, gate, 1, shortcut, 1, y, 1);
 }
 
 void orc_squeeze(const int32_t* in, int C, int H, int W, int32_t* out) {
@@ -142,6 +172,7 @@ int orc_model_load(const void* blob, size_t bytes, orc_model** out) {
     m->H = (int)h[3]; m->W = (int)h[4]; m->levels = (int)h[5]; m->couplings = (int)h[6];
     m->family = (int)h[7]; m->width = (int)h[8]; m->depth = (int)h[9]; m->has_heads = (int)h[10];
     m->n_nets = (int)h[11];
+    m->act_unsigned = (int)(h[12] & 1u);
     if (m->levels < 1 || m->levels > 8 || m->H <= 0 || m->W <= 0 || (m->H % (1 << m->levels)) ||
         (m->W % (1 << m->levels)) || m->n_nets < 1 || m->n_nets > 4096 || m->family > 2) {
         orc_model_free(m); return -3;
@@ -225,10 +256,15 @@ int64_t orc_model_d_codes(const orc_model* m) {
 /* ---- networks --------------------------------------------------------------- */
 
 /* One conv layer on one image: accumulate (Eq. 4), then the integer epilogue. */
-static void run_layer(const orc_layer* L, const int8_t* x, int h, int w, const int8_t* shortcut,
-                      int32_t* acc, int8_t* y) {
-    orc_conv_acc(x, L->C_in, h, w, L->W, L->C_out, L->k, L->bias, L->gate, acc);
-    orc_epilogue(acc, L->C_out, h * w, L->M, L->shift, L->gate, L->relu, shortcut, y);
+/* In the unsigned format (Eq. 3) a tensor that leaves a ReLU holds codes 0..255; xu / su say
+ * whether the input and the shortcut are such tensors, and the output is one iff this layer has
+ * a ReLU. Returns whether the output is unsigned. */
+static int run_layer(const orc_model* m, const orc_layer* L, const int8_t* x, int xu, int h, int w,
+                     const int8_t* shortcut, int su, int32_t* acc, int8_t* y) {
+    const int yu = m->act_unsigned && L->relu;
+    conv_acc_any(x, xu, L->C_in, h, w, L->W, L->C_out, L->k, L->bias, L->gate, acc);
+    epilogue_any(acc, L->C_out, h * w, L->M, L->shift, L->gate, L->relu, shortcut, su, y, yu);
+    return yu;
 }
 
 int orc_net_eval(const orc_model* m, int n, const int32_t* xa, int h, int w, int8_t* out) {
@@ -249,8 +285,8 @@ int orc_net_eval(const orc_model* m, int n, const int32_t* xa, int h, int w, int
         /* conv -> ReLU -> conv */
         if (nl != 2) { rc = -3; goto done; }
         int8_t* f = (int8_t*)malloc((size_t)Ls[0].C_out * hw);
-        run_layer(&Ls[0], q, h, w, NULL, acc, f);
-        run_layer(&Ls[1], f, h, w, NULL, acc, out);
+        const int fu = run_layer(m, &Ls[0], q, 0, h, w, NULL, 0, acc, f);
+        run_layer(m, &Ls[1], f, fu, h, w, NULL, 0, acc, out);
         free(f);
     } else if (m->family == FAM_RESNET) {
         /* conv_in, blocks r <- ReLU(r + conv1x1(ReLU(conv3x3(r)))) (Eq. 2), conv_out */
@@ -259,13 +295,13 @@ int orc_net_eval(const orc_model* m, int n, const int32_t* xa, int h, int w, int
         int8_t* r = (int8_t*)malloc((size_t)Wd * hw);
         int8_t* t1 = (int8_t*)malloc((size_t)Wd * hw);
         int8_t* r2 = (int8_t*)malloc((size_t)Wd * hw);
-        run_layer(&Ls[0], q, h, w, NULL, acc, r);
+        int ru = run_layer(m, &Ls[0], q, 0, h, w, NULL, 0, acc, r);
         for (int l = 1; l + 1 < nl; l += 2) {
-            run_layer(&Ls[l], r, h, w, NULL, acc, t1);
-            run_layer(&Ls[l + 1], t1, h, w, r, acc, r2);
+            const int tu = run_layer(m, &Ls[l], r, ru, h, w, NULL, 0, acc, t1);
+            ru = run_layer(m, &Ls[l + 1], t1, tu, h, w, r, ru, acc, r2);
             memcpy(r, r2, (size_t)Wd * hw);
         }
-        run_layer(&Ls[nl - 1], r, h, w, NULL, acc, out);
+        run_layer(m, &Ls[nl - 1], r, ru, h, w, NULL, 0, acc, out);
         free(r); free(t1); free(r2);
     } else {
         /* dense: f0 = conv_in; g = conv1x1(concat(f0..f_{l-1})); f_l = conv3x3(g);
@@ -275,13 +311,14 @@ int orc_net_eval(const orc_model* m, int n, const int32_t* xa, int h, int w, int
         const int depth = (nl - 2) / 2;
         int8_t* cat = (int8_t*)malloc((size_t)(depth + 1) * Wd * hw);
         int8_t* g = (int8_t*)malloc((size_t)Wd * hw);
-        run_layer(&Ls[0], q, h, w, NULL, acc, cat);
+        /* every feature of the concatenation leaves a ReLU, so the whole of it has one format */
+        const int cu = run_layer(m, &Ls[0], q, 0, h, w, NULL, 0, acc, cat);
         for (int l = 1; l <= depth; ++l) {
             if (Ls[2 * l - 1].C_in != l * Wd || Ls[2 * l].C_in != Wd) { rc = -3; break; }
-            run_layer(&Ls[2 * l - 1], cat, h, w, NULL, acc, g);
-            run_layer(&Ls[2 * l], g, h, w, NULL, acc, cat + (size_t)l * Wd * hw);
+            const int gu = run_layer(m, &Ls[2 * l - 1], cat, cu, h, w, NULL, 0, acc, g);
+            if (run_layer(m, &Ls[2 * l], g, gu, h, w, NULL, 0, acc, cat + (size_t)l * Wd * hw) != cu) { rc = -3; break; }
         }
-        if (!rc) run_layer(&Ls[nl - 1], cat, h, w, NULL, acc, out);
+        if (!rc) run_layer(m, &Ls[nl - 1], cat, cu, h, w, NULL, 0, acc, out);
         free(cat); free(g);
     }
 done:

@@ -48,9 +48,20 @@ int32_t orc_sat8(int64_t u);
 void orc_conv_acc(const int8_t* x, int D, int h, int w, const int8_t* W, int C, int k,
                   const int32_t* bias, const uint8_t* gate, int32_t* acc);
 
+/* The same with the input read as unsigned codes 0..255 (Eq. 3: the hybrid format keeps signed
+ * 8-bit weights and may use unsigned 8-bit activations). */
+void orc_conv_acc_u8(const uint8_t* x, int D, int h, int w, const int8_t* W, int C, int k,
+                     const int32_t* bias, const uint8_t* gate, int32_t* acc);
+
 /* Epilogue of one conv layer: y = sat8(relu?((gate ? rq(acc; M_c, s_c) : 0) + shortcut?)). */
 void orc_epilogue(const int32_t* acc, int C, int hw, const int32_t* M, const uint8_t* shift,
                   const uint8_t* gate, int relu, const int8_t* shortcut, int8_t* y);
+
+/* Unsigned format: y = min(255, relu((gate ? rq(acc) : 0) + shortcut?)), shortcut and y unsigned.
+ * A model whose blob header sets the unsigned flag stores every tensor that leaves a ReLU this
+ * way; tensors without a ReLU (the input quantiser's, the translation, the head codes) stay signed. */
+void orc_epilogue_u8(const int32_t* acc, int C, int hw, const int32_t* M, const uint8_t* shift,
+                     const uint8_t* gate, const uint8_t* shortcut, uint8_t* y);
 
 /* Space-to-depth 2x2: out[4c+2dy+dx, i, j] = in[c, 2i+dy, 2j+dx]; and its inverse. */
 void orc_squeeze(const int32_t* in, int C, int H, int W, int32_t* out);

@@ -28,6 +28,7 @@ class FlowConfig:
     seed_id: int = 0
     block_k2: int = 1       # resnet family: kernel of a block's second conv (the paper's own blocks use 3)
     keep_levels: tuple = () # per-level keep fractions (level 1 first); empty = `keep` everywhere
+    act_unsigned: bool = False   # post-ReLU activations are unsigned 8-bit codes 0..255 (the paper's own format)
 
     def keep_at(self, level):
         return self.keep_levels[level - 1] if self.keep_levels else self.keep
@@ -153,6 +154,14 @@ CONFIGS = {
     "paper_res64": FlowConfig("paper_res64", 64, 64, 256, 4, 8, RESNET, 128, 8, True, seed_id=16, block_k2=3),
     "paper_iodf64": FlowConfig("paper_iodf64", 64, 64, 256, 4, 8, RESNET, 128, 8, True, seed_id=17, block_k2=3,
                                keep=0.5, keep_levels=(0.75, 0.625, 0.375, 0.25)),
+    # unsigned post-ReLU activations (Eq. 3): the three families, a gated one, and the paper's network
+    "mini_dense_u": FlowConfig("mini_dense_u", 16, 16, 5, 2, 2, DENSE, 64, 3, True, seed_id=19, act_unsigned=True),
+    "mini_resnet_gu": FlowConfig("mini_resnet_gu", 16, 16, 3, 2, 2, RESNET, 32, 2, True, keep=0.5, seed_id=20,
+                                 act_unsigned=True),
+    "cfg1_u": FlowConfig("cfg1_u", 8, 8, 1, 1, 2, PLAIN, 32, 0, False, image_kind="uniform", seed_id=21,
+                         act_unsigned=True),
+    "paper_iodf64_u": FlowConfig("paper_iodf64_u", 64, 64, 256, 4, 8, RESNET, 128, 8, True, seed_id=17, block_k2=3,
+                                 keep=0.5, keep_levels=(0.75, 0.625, 0.375, 0.25), act_unsigned=True),
     "mini_paper_g": FlowConfig("mini_paper_g", 16, 16, 3, 2, 2, RESNET, 32, 3, True, seed_id=18, block_k2=3,
                                keep=0.5, keep_levels=(0.75, 0.375)),
 }

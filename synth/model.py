@@ -149,12 +149,14 @@ def _gen_network(cfg, seed, idx, kind, level, c_level, c_in, c_out, n_prev, mode
         else:
             bias = np.zeros(co)
         bias = np.clip(bias, -(2 ** 30) + 1, 2 ** 30 - 1).astype(np.int32)
+        # unsigned post-ReLU codes have one more bit of range
+        top = 255.0 if (cfg.act_unsigned and relu) else 127.0
         if last:
             target = 16.0 if kind == 0 else 127.0
         elif shortcut:
-            target = 64.0
+            target = (top + 1.0) / 2.0
         else:
-            target = 127.0
+            target = top
         if mode == "zero":
             scale = np.ones(co)
         else:
@@ -201,7 +203,7 @@ def make_blob(cfg, seed=None, mode="random", threads=None):
     blob = np.zeros(int(offs[-1]), dtype=np.uint8)
     hdr = np.array([BLOB_MAGIC[0], BLOB_MAGIC[1], 1, cfg.H, cfg.W, cfg.levels, cfg.couplings,
                     cfg.family, cfg.width, cfg.depth, 1 if cfg.heads else 0, len(nets),
-                    0, 0, 0, 0], dtype=np.uint32)
+                    1 if cfg.act_unsigned else 0, 0, 0, 0], dtype=np.uint32)
     blob[:64] = hdr.view(np.uint8)
     jobs = []
     n_prev = 0
@@ -230,7 +232,7 @@ def parse_blob(blob):
     if (int(h[0]), int(h[1])) != BLOB_MAGIC or int(h[2]) != 1:
         raise ValueError("not an IODF model blob")
     model = dict(H=int(h[3]), W=int(h[4]), levels=int(h[5]), couplings=int(h[6]), family=int(h[7]),
-                 width=int(h[8]), depth=int(h[9]), has_heads=int(h[10]), nets=[])
+                 width=int(h[8]), depth=int(h[9]), has_heads=int(h[10]), act_unsigned=int(h[12]) & 1, nets=[])
     pos = 64
 
     def take(nbytes, dtype):
@@ -275,7 +277,8 @@ def pack_blob(model):
 
     nets = model["nets"]
     put([BLOB_MAGIC[0], BLOB_MAGIC[1], 1, model["H"], model["W"], model["levels"], model["couplings"],
-         model["family"], model["width"], model["depth"], model["has_heads"], len(nets), 0, 0, 0, 0],
+         model["family"], model["width"], model["depth"], model["has_heads"], len(nets),
+         model.get("act_unsigned", 0), 0, 0, 0],
         np.uint32)
     for net in nets:
         put([net["kind"], net["level"], net["C"], net["C_in"], net["C_out"], len(net["layers"])], np.uint32)

@@ -427,3 +427,123 @@ def test_generated_constants_give_live_translations(name):
     assert 1.5 < t.std() < 12.0 and (np.abs(t) >= 127).mean() < 0.01
     if cfg.heads:
         assert 15.0 < codes.astype(np.int64).std() < 70.0
+
+
+# ---- unsigned activation format (Eq. 3) --------------------------------------------------
+
+def test_unsigned_conv_matches_a_library_convolution():
+    import torch
+    rng = np.random.default_rng(11)
+    x = rng.integers(0, 256, (5, 6, 7)).astype(np.uint8)        # codes above 127 must count as 128..255
+    W = rng.integers(-128, 128, (4, 5, 3, 3)).astype(np.int8)
+    b = rng.integers(-1000, 1000, 4).astype(np.int32)
+    got = oracle.conv_acc_u8(x, W, b)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(x.astype(np.float64))[None], torch.from_numpy(W.astype(np.float64)),
+                                     torch.from_numpy(b.astype(np.float64)), padding=1)[0].numpy()
+    assert np.array_equal(got, ref.astype(np.int64))
+    # and it is not the signed reading of the same bytes
+    assert not np.array_equal(got, oracle.conv_acc(x.view(np.int8), W, b))
+
+
+def test_unsigned_epilogue_by_hand():
+    acc = np.array([[[-5, 0, 100, 254, 255, 256, 300, 1000]]], np.int32)
+    M, sh = np.array([ONE], np.int32), np.array([30], np.uint8)          # rescale by exactly 1
+    assert oracle.epilogue_u8(acc, M, sh).reshape(-1).tolist() == [0, 0, 100, 254, 255, 255, 255, 255]
+    sc = np.array([[[200, 200, 200, 200, 0, 7, 255, 0]]], np.uint8)      # shortcut codes are unsigned too
+    assert oracle.epilogue_u8(acc, M, sh, shortcut=sc).reshape(-1).tolist() == [195, 200, 255, 255, 255, 255, 255, 255]
+    half = np.array([ONE], np.int32), np.array([31], np.uint8)           # x 1/2, half away from zero
+    assert oracle.epilogue_u8(np.array([[[509, 510, 511, -1, 3]]], np.int32), *half).reshape(-1).tolist() == [255, 255, 255, 0, 2]
+
+
+def test_unsigned_resnet_wiring_saturates_at_255():
+    # the doubling network of the signed pin: in the unsigned format the stream saturates at 255
+    Wd, depth = 6, 4
+    cfg = _one_level(RESNET, Wd, depth)
+    model = parse_blob(make_blob(cfg, mode="zero"))
+    model["act_unsigned"] = 1
+    net = model["nets"][0]
+    net["M_in"][:] = ONE
+    net["s_in"][:] = 30
+    Ls = net["layers"]
+    for L in Ls:
+        _unit(L)
+    rng = np.random.default_rng(2)
+    xa = rng.integers(-30, 60, (6, 4, 4)).astype(np.int32)
+    for c in range(Wd):
+        Ls[0]["W"][c, c, 1, 1] = 1
+    r = np.maximum(xa.astype(np.int64), 0)
+    for b in range(depth):
+        c1, c2 = Ls[1 + 2 * b], Ls[2 + 2 * b]
+        for c in range(Wd):
+            c1["W"][c, c, 1, 2] = 1
+            c2["W"][c, (c + 1) % Wd, 0, 0] = 1
+        t1 = np.stack([_shift2d(r[c], 0, 1) for c in range(Wd)])
+        r = np.minimum(255, r + np.roll(t1, -1, axis=0))
+    for c in range(6):
+        Ls[-1]["W"][c, c, 1, 1] = -1                  # the translation itself is a signed code
+    got = oracle.Model(pack_blob(model)).net_eval(0, xa, 6)
+    assert (r == 255).any() and ((r > 127) & (r < 255)).any()
+    assert np.array_equal(got, np.maximum(-r, -128))
+
+
+def test_unsigned_dense_wiring_carries_codes_above_127():
+    Wd, depth = 8, 2
+    cfg = _one_level(DENSE, Wd, depth)
+    model = parse_blob(make_blob(cfg, mode="zero"))
+    model["act_unsigned"] = 1
+    net = model["nets"][0]
+    net["M_in"][:] = ONE
+    net["s_in"][:] = 30
+    Ls = net["layers"]
+    for L in Ls:
+        _unit(L)
+    rng = np.random.default_rng(5)
+    xa = rng.integers(-100, 100, (6, 4, 4)).astype(np.int32)
+    relu = lambda a: np.maximum(a, 0)
+    feats = []
+    f0 = np.zeros((Wd, 4, 4), dtype=np.int64)
+    for c in range(Wd):
+        Ls[0]["W"][c, c % 6, 1, 1] = 3                      # up to 297: saturates at 255
+        f0[c] = np.minimum(255, relu(3 * xa[c % 6]))
+    feats.append(f0)
+    for l in range(1, depth + 1):
+        cat = np.concatenate(feats)
+        g = np.zeros((Wd, 4, 4), dtype=np.int64)
+        for c in range(Wd):
+            sel = (3 * c + 5 * l) % (l * Wd)
+            Ls[2 * l - 1]["W"][c, sel, 0, 0] = 1
+            g[c] = cat[sel]
+        f = np.zeros((Wd, 4, 4), dtype=np.int64)
+        for c in range(Wd):
+            ky, kx = c % 3, (c // 3) % 3
+            Ls[2 * l]["W"][c, (c + 1) % Wd, ky, kx] = 1
+            f[c] = _shift2d(g[(c + 1) % Wd], ky - 1, kx - 1)
+        feats.append(f)
+    cat = np.concatenate(feats)
+    want = np.zeros((6, 4, 4), dtype=np.int64)
+    for c in range(6):
+        sel = (7 * c + 3) % ((depth + 1) * Wd)
+        Ls[-1]["W"][c, sel, 2, 0] = 1
+        Ls[-1]["shift"][:] = 31                             # halve so that 128..255 survive the signed output
+        want[c] = _shift2d(cat[sel], 1, -1)
+    got = oracle.Model(pack_blob(model)).net_eval(0, xa, 6)
+    assert (cat > 127).any()
+    halves = np.array([[_half_away(Fraction(int(v), 2)) for v in row] for row in want.reshape(6, -1)]).reshape(6, 4, 4)
+    assert np.array_equal(got, np.minimum(halves, 127))        # 255 / 2 rounds to 128 and saturates
+
+
+@pytest.mark.parametrize("name", ["mini_dense_u", "mini_resnet_gu", "cfg1_u"])
+def test_unsigned_flows_round_trip_and_use_the_extra_bit(name):
+    cfg = CONFIGS[name]
+    blob = make_blob(cfg)
+    assert parse_blob(blob)["act_unsigned"] == 1
+    m = oracle.Model(blob)
+    x = make_images(cfg, batch=2)
+    z, codes = m.forward(x)
+    x2, errs = m.inverse(z, x.shape[1:])
+    assert errs == 0 and np.array_equal(x, x2)
+    # the same bytes read as a signed-format model give another flow: codes above 127 exist and matter
+    signed = blob.copy()
+    signed[48:52] = 0
+    z_s, _ = oracle.Model(signed).forward(x)
+    assert not np.array_equal(z, z_s)
