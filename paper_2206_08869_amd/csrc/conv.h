@@ -59,6 +59,9 @@ struct ConvArgs {
     // rq_fast only: smallest accumulator (bias included) whose requantised value reaches 127, saturated
     // to INT32_MAX; lets a ReLU layer clamp before the multiply instead of after it
     const int32_t* clamp_hi;
+    // Unsigned codes (0..255, stored as code - 128): out_unsigned saturates MODE_ACT results to [0, 255]
+    // (the layer then has a ReLU); sc_unsigned says the shortcut bytes are such codes.
+    int out_unsigned, sc_unsigned;
     int log2_w, log2_hw;  // filled by launch_conv: log2 of w and of h*w when both are powers of two, else -1
     int32_t* partial;  // optional split-K scratch: int32 [npix][n_pad], all zero between launches
     int n_store;   // channels written (<= n_pad); multiple of 4 in MODE_ACT

@@ -146,20 +146,21 @@ __device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc
                         "src1_sel:DWORD" : "+v"(p4) : "v"(Sq[g][2]), "v"(q[2]));
                     asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD "
                         "src1_sel:DWORD" : "+v"(p4) : "v"(Sq[g][3]), "v"(q[3]));
-                    pk[g] = p4;
+                    pk[g] = a.out_unsigned ? p4 ^ 0x80808080u : p4;  // code u is stored as u - 128
                     return;
                 } else {
                     int sc = 0;
                     if (a.shortcut && live) sc = *(const int*)(orow + g * 8 + half * 4);
+                    const int sc_add = (a.shortcut && a.sc_unsigned) ? 128 : 0;  // stored byte = code - 128
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int av = acc[tc][tp][g * 4 + e] + Bq[g][e];
                         const int sgn = av >> 31;
                         int r = rq_fast_abs((unsigned)((av ^ sgn) - sgn), Mq[g][e], Sq[g][e]);
                         r = (r ^ sgn) - sgn;
-                        r += (int)(int8_t)(sc >> (8 * e));
+                        r += (int)(int8_t)(sc >> (8 * e)) + sc_add;
                         if (a.relu) r = r < 0 ? 0 : r;
-                        y[e] = sat8_dev(r);
+                        y[e] = a.out_unsigned ? (r > 255 ? 255 : r) - 128 : sat8_dev(r);
                     }
                 }
                 pk[g] = ((unsigned)y[0] & 0xffu) | (((unsigned)y[1] & 0xffu) << 8) | (((unsigned)y[2] & 0xffu) << 16) |
@@ -196,13 +197,13 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs& a, v16i (&acc)[TC]
                 constexpr int g = decltype(g_)::value;
                 const int nb = ch_base + tc * 32 + g * 8 + half * 4;
                 if (nb >= a.n_store) return;
+                const v4i B4 = *(const v4i*)(a.bias + nb);
                 if (a.mode == MODE_RAW) {  // n_pad is a multiple of 64, so the quad is in bounds
-                    const v4i r4 = {acc[tc][tp][g * 4 + 0], acc[tc][tp][g * 4 + 1], acc[tc][tp][g * 4 + 2],
-                                    acc[tc][tp][g * 4 + 3]};
+                    const v4i r4 = {acc[tc][tp][g * 4 + 0] + B4[0], acc[tc][tp][g * 4 + 1] + B4[1],
+                                    acc[tc][tp][g * 4 + 2] + B4[2], acc[tc][tp][g * 4 + 3] + B4[3]};
                     *(v4i*)(a.partial + (long long)m * a.n_pad + nb) = r4;
                     return;
                 }
-                const v4i B4 = *(const v4i*)(a.bias + nb);
                 const v4i M4 = *(const v4i*)(a.mul + nb);
                 const v4i S4 = *(const v4i*)(a.shift + nb) + (a.rq_fast ? 32 : 0);
                 int v[4];
@@ -219,9 +220,9 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs& a, v16i (&acc)[TC]
                         const long long pp = (long long)bi * ((a.h + 2) * (a.w + 2)) + (ii + 1) * (a.w + 2) + (ji + 1);
                         int8_t* o = a.out + (long long)(a.out_chunk0 + (ch >> 6)) * a.out_plane + pp * 64 + (ch & 63);
                         int y = v[e];
-                        if (a.shortcut) y += (int)*o;
+                        if (a.shortcut) y += (int)*o + (a.sc_unsigned ? 128 : 0);
                         if (a.relu) y = y < 0 ? 0 : y;
-                        *o = (int8_t)sat8_dev(y);
+                        *o = (int8_t)(a.out_unsigned ? (y > 255 ? 255 : y) - 128 : sat8_dev(y));
                     }
                 } else if (a.mode == MODE_COUPLE) {
 #pragma unroll
@@ -515,9 +516,9 @@ __global__ void conv_splitk_finish(const ConvArgs a) {
             const int bi = m / hw, qi = m - bi * hw, ii = qi / a.w, ji = qi - ii * a.w;
             const long long pp = (long long)bi * ((a.h + 2) * (a.w + 2)) + (ii + 1) * (a.w + 2) + (ji + 1);
             int8_t* o = a.out + (long long)(a.out_chunk0 + (ch >> 6)) * a.out_plane + pp * 64 + (ch & 63);
-            if (a.shortcut) y += (int)*o;
+            if (a.shortcut) y += (int)*o + (a.sc_unsigned ? 128 : 0);
             if (a.relu) y = y < 0 ? 0 : y;
-            *o = (int8_t)sat8_dev(y);
+            *o = (int8_t)(a.out_unsigned ? (y > 255 ? 255 : y) - 128 : sat8_dev(y));
         } else if (a.mode == MODE_COUPLE) {
             if (a.relu) y = y < 0 ? 0 : y;
             a.state[(long long)m * a.state_c + a.idx_b[c]] += a.sign * sat8_dev(y);

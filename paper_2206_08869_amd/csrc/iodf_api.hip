@@ -59,6 +59,7 @@ struct HostNet {
 
 struct HostModel {
     int H, W, levels, couplings, family, width, depth, has_heads;
+    int act_unsigned;  // tensors that leave a ReLU hold unsigned codes 0..255 (Eq. 3)
     std::vector<HostNet> nets;
 };
 
@@ -71,6 +72,8 @@ int parse_blob(const uint8_t* p, size_t bytes, HostModel& m) {
     m.H = (int)h[3]; m.W = (int)h[4]; m.levels = (int)h[5]; m.couplings = (int)h[6]; m.family = (int)h[7];
     m.width = (int)h[8]; m.depth = (int)h[9]; m.has_heads = (int)h[10];
     const uint32_t n_nets = h[11];
+    if (h[12] > 1u || h[13] || h[14] || h[15]) return IODF_E_BLOB;  // unknown format flags
+    m.act_unsigned = (int)h[12];
     if (m.levels < 1 || m.levels > 8 || m.couplings < 1 || m.couplings > 1024 || m.H < 2 || m.W < 2 || m.H > 8192 ||
         m.W > 8192 || (m.H % (1 << m.levels)) || (m.W % (1 << m.levels)) || m.family < 0 || m.family > 2 ||
         m.has_heads > 1 || m.has_heads < 0)
@@ -163,6 +166,13 @@ int check_shapes(const HostModel& m) {
             return IODF_E_SHAPE;
         for (int c = 0; c < N.C_out; ++c)
             if (!L[nl - 1].gate[c]) return IODF_E_SHAPE;  // the translation / code channels cannot be gated
+        // unsigned format: every hidden tensor must leave a ReLU (one format per activation buffer),
+        // the translation / codes stay signed
+        if (m.act_unsigned) {
+            for (int l = 0; l + 1 < nl; ++l)
+                if (!L[l].relu) return IODF_E_SHAPE;
+            if (L[nl - 1].relu) return IODF_E_SHAPE;
+        }
         const int Wd = L[0].C_out;
         if (m.family == FAM_PLAIN) {
             if (nl != 2 || L[1].C_in != Wd) return IODF_E_SHAPE;
@@ -195,6 +205,10 @@ struct DevLayer {
     int out_buf, out_off;  // output tensor (MODE_ACT)
     size_t wgt_off, bias_off, mul_off, shift_off;  // byte offsets into the parameter arena
     size_t hi_off = (size_t)-1;                    // rq_fast layers: clamp bound per channel
+    // Unsigned format: a code u in 0..255 is stored as the byte u - 128 and planes are bordered with
+    // -128, so that the int8 matrix cores see u - 128 everywhere; a layer reading such a tensor adds
+    // 128 * (sum of its weights) to its bias, a layer writing one saturates to [0, 255] and stores u - 128.
+    bool in_unsigned = false, out_unsigned = false, sc_unsigned = false;
     // tap-expanded 3x3 last layer (see TapSumArgs): the GEMM is 1x1 with 9 * c_out rows and
     // stores raw accumulators; these are the constants of the summing pass
     int expand_c_out = 0, final_mode = 0;
@@ -276,7 +290,12 @@ void pack_layer(Arena& A, const HostLayer& L, const std::vector<int>& rows, cons
             for (int t = 0; t < taps; ++t)
                 w[(((size_t)(pc >> 6) * taps + t) * D.n_pad + n) * 64 + (pc & 63)] = src[(size_t)c * taps + t];
         }
-        bias[n] = L.bias[r];
+        long long fold = 0;  // sum of the row's kept weights
+        if (D.in_unsigned)
+            for (int c = 0; c < L.C_in; ++c)
+                if (colpos[c] >= 0)
+                    for (int t = 0; t < taps; ++t) fold += src[(size_t)c * taps + t];
+        bias[n] = (int32_t)(L.bias[r] + 128 * fold);  // |bias| < 2^30 and 128 * 127 * K < 2^30 for K < 66000
         mul[n] = L.M[r];
         sh[n] = L.shift[r];
     }
@@ -289,9 +308,10 @@ void pack_layer(Arena& A, const HostLayer& L, const std::vector<int>& rows, cons
         if (D.rq_fast) sh[n] -= 32;
     }
     if (D.rq_fast) {
-        // Smallest accumulator a >= 0 with (floor(a * M / 2^32) + 2^(sh-1)) >> sh >= 127, i.e.
-        // a * M >= (127 * 2^sh - 2^(sh-1)) * 2^32. The rescale factor M / 2^(32+sh) is below 1, so the
-        // result there is exactly 127; beyond int32 no accumulator reaches 127 at all.
+        // Smallest accumulator a >= 0 with (floor(a * M / 2^32) + 2^(sh-1)) >> sh >= top (127, or 255 for
+        // unsigned codes), i.e. a * M >= (top * 2^sh - 2^(sh-1)) * 2^32. The rescale factor
+        // M / 2^(32+sh) is below 1, so the result there is exactly top; beyond int32 no accumulator
+        // reaches it at all.
         D.hi_off = A.alloc(4 * (size_t)D.n_pad);
         int32_t* hi = (int32_t*)(A.host.data() + D.hi_off);
         mul = (int32_t*)(A.host.data() + D.mul_off);  // the arena may have moved
@@ -299,7 +319,8 @@ void pack_layer(Arena& A, const HostLayer& L, const std::vector<int>& rows, cons
         for (int n = 0; n < D.n_pad; ++n) {
             hi[n] = INT32_MAX;
             if (mul[n] <= 0) continue;
-            const unsigned __int128 need = ((unsigned __int128)((127ULL << sh[n]) - (1ULL << (sh[n] - 1)))) << 32;
+            const unsigned long long top = D.out_unsigned ? 255ULL : 127ULL;
+            const unsigned __int128 need = ((unsigned __int128)((top << sh[n]) - (1ULL << (sh[n] - 1)))) << 32;
             const unsigned __int128 a = (need + (unsigned)mul[n] - 1) / (unsigned)mul[n];
             if (a < (unsigned __int128)INT32_MAX) hi[n] = (int32_t)(uint64_t)a;
         }
@@ -325,7 +346,7 @@ void pack_last_expanded(Arena& A, const HostLayer& L, const std::vector<int>& co
     D.expand_c_out = co;
     D.final_mode = final_mode;
     D.wgt_off = A.alloc((size_t)D.n_pad * cin_pad);
-    D.bias_off = A.alloc(4 * (size_t)D.n_pad);   // unused by the raw GEMM, kept valid
+    D.bias_off = A.alloc(4 * (size_t)D.n_pad);   // added to the raw accumulators: 0, or the unsigned-input fold
     D.mul_off = A.alloc(4 * (size_t)D.n_pad);
     D.shift_off = A.alloc(4 * (size_t)D.n_pad);
     D.fin_bias_off = A.alloc(4 * (size_t)co);
@@ -334,13 +355,17 @@ void pack_last_expanded(Arena& A, const HostLayer& L, const std::vector<int>& co
     int8_t* w = (int8_t*)(A.host.data() + D.wgt_off);
     int live = 0;
     for (int c = 0; c < L.C_in; ++c) live += colpos[c] >= 0;
+    int32_t* xb = (int32_t*)(A.host.data() + D.bias_off);
     for (int r = 0; r < co; ++r)
         for (int c = 0; c < L.C_in; ++c) {
             const int pc = colpos[c];
             if (pc < 0) continue;
-            for (int t = 0; t < 9; ++t)
-                w[((size_t)(pc >> 6) * D.n_pad + (size_t)(t * co + r)) * 64 + (pc & 63)] =
-                    L.W[((size_t)r * L.C_in + c) * 9 + t];
+            for (int t = 0; t < 9; ++t) {
+                const int8_t wv = L.W[((size_t)r * L.C_in + c) * 9 + t];
+                w[((size_t)(pc >> 6) * D.n_pad + (size_t)(t * co + r)) * 64 + (pc & 63)] = wv;
+                // a tap that falls outside the image is skipped by the summing pass, fold and all
+                if (D.in_unsigned) xb[t * co + r] += 128 * (int32_t)wv;
+            }
         }
     int32_t* fb = (int32_t*)(A.host.data() + D.fin_bias_off);
     int32_t* fm = (int32_t*)(A.host.data() + D.fin_mul_off);
@@ -366,6 +391,11 @@ void plan_net(Arena& A, const HostModel& m, const HostNet& N, DevNet& D, int buf
     D.M_in = N.M_in; D.s_in = N.s_in;
     D.cin_pad0 = round64(N.C_in);
     D.layers.resize(nl);
+    for (int l = 0; l < nl; ++l) {  // read by the packers below
+        D.layers[l].in_unsigned = m.act_unsigned && l > 0;
+        D.layers[l].out_unsigned = m.act_unsigned && l + 1 < nl;
+        D.layers[l].sc_unsigned = m.act_unsigned && L[l].shortcut;
+    }
     buf_w[BUF_XQ] = std::max(buf_w[BUF_XQ], D.cin_pad0);
     const int last_mode = N.kind == 0 ? MODE_COUPLE : MODE_CODES;
     // the last layer: tap-expanded when it is 3x3 (every family here), else a plain GEMM
@@ -573,6 +603,8 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
         a.shift = (const int32_t*)(ctx->params + L.shift_off);
         a.n_store = L.n_store;
         a.rq_fast = L.rq_fast;
+        a.out_unsigned = L.out_unsigned && L.mode == MODE_ACT;
+        a.sc_unsigned = L.sc_unsigned;
         a.clamp_hi = L.hi_off == (size_t)-1 ? nullptr : (const int32_t*)(ctx->params + L.hi_off);
         if (L.mode != MODE_ACT && (size_t)npix * L.n_pad <= ctx->partial_elems) a.partial = ctx->partial;
         a.mode = L.mode;
@@ -755,8 +787,8 @@ int iodf_init(iodf_ctx** out, const void* model_blob, size_t blob_bytes, int dev
         for (int b = 0; b < NUM_BUFS && ok; ++b) {
             const size_t bytes = (size_t)ctx->plane[lv] * (size_t)(std::max(ctx->buf_w[lv][b], 64) / 64);
             ok = dev_alloc((void**)&ctx->buf[lv][b], bytes);
-            if (ok) {  // the borders (and everything else) start as zeros
-                e = hipMemset(ctx->buf[lv][b], 0, bytes);
+            if (ok) {  // the borders (and everything else) start as code 0: byte 0, or -128 for unsigned tensors
+                e = hipMemset(ctx->buf[lv][b], (hm.act_unsigned && b != BUF_XQ) ? 0x80 : 0, bytes);
                 if (e != hipSuccess) { g_last_hip = (int)e; ok = false; }
             }
         }

@@ -68,6 +68,15 @@ def test_init_rejects_bad_arguments_and_blobs_on_the_host():
     assert _init_code(edited(lambda m: m["nets"][0]["layers"][0]["gate"].__setitem__(slice(None), 0))) == -2
     # well formed but not a valid flow: the translation channels may not be gated
     assert _init_code(edited(lambda m: m["nets"][0]["layers"][1]["gate"].__setitem__(0, 0))) == -3
+    # unknown format flags in the header; an unsigned-format model whose hidden layer lacks a ReLU
+    bad = good.copy(); bad[52] = 1
+    assert _init_code(bad) == -2
+    bad = good.copy(); bad[48] = 2
+    assert _init_code(bad) == -2
+    def unsigned_without_relu(m):
+        m["act_unsigned"] = 1
+        m["nets"][0]["layers"][0]["flags"] &= ~1
+    assert _init_code(edited(unsigned_without_relu)) == -3
     # wrong number of networks for the declared structure
     assert _init_code(edited(lambda m: m["nets"].pop())) == -3
     # wrong wiring: second conv of a plain t() must read the first conv's width

@@ -80,6 +80,12 @@ def test_paper_network_pruned_sampled(capsys):
 
 
 @pytest.mark.timeout(600)
+def test_paper_network_pruned_unsigned_sampled(capsys):
+    # the same network with the paper's unsigned activation codes (0..255 after every ReLU)
+    _sampled(capsys, "paper_iodf64_u", CONFIGS["paper_iodf64_u"].batch, sample=(1, 254), invariance=(100,), chunk=97)
+
+
+@pytest.mark.timeout(600)
 def test_paper_network_32_sampled(capsys):
     _sampled(capsys, "paper_res32", CONFIGS["paper_res32"].batch, sample=(0, 300, 511), invariance=(9,), chunk=129)
 
