@@ -266,10 +266,11 @@ def main():
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "%s: %d x 3x%dx%d u8 filtered-noise images, %d levels x %d couplings, %s t() width %d "
-                               "depth %d, keep %.2f, prior heads %s; %s" %
+                               "depth %d, keep %.2f, prior heads %s, %s activation codes; %s" %
                                (cfg.name, batch, cfg.H, cfg.W, cfg.levels, cfg.couplings,
                                 ["plain", "residual", "dense"][cfg.family], cfg.width, cfg.depth, cfg.keep,
-                                "on" if cfg.heads else "off", args.direction),
+                                "on" if cfg.heads else "off", "unsigned" if cfg.act_unsigned else "signed",
+                                args.direction),
                    "batch": batch, "macs_per_image": macs_img},
         "whole_path_tops": round(whole_tops, 2),
         "whole_path_frac_of_int8_peak": round(whole_tops / INT8_PEAK_TOPS, 4),

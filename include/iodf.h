@@ -77,7 +77,7 @@ enum {
  *   model_blob   host; little-endian, 4-byte aligned fields:
  *                  header 16 x u32: 'IODF','BLB1', version 1, H, W, levels, couplings per
  *                    level, family (0 plain, 1 residual, 2 dense), width, depth, has_heads,
- *                    n_nets, 4 x reserved
+ *                    n_nets, act_unsigned (0 | 1), 3 x reserved (0)
  *                  per network in flow order (level 1 couplings, level 1 head, level 2, ...):
  *                    8 x 32 bit: kind (0 coupling, 1 head), level, C_level, C_in, C_out,
  *                    n_layers, M_in (i32), s_in; then i32 perm[C_level] for couplings;
@@ -89,6 +89,10 @@ enum {
  *                so they cost nothing at inference.
  *   device_ordinal  HIP device to run on.
  *   max_batch    largest batch later calls may pass (sizes the workspace); >= 1.
+ * act_unsigned = 1 selects the paper's hybrid number format (Sec. 4.1, Eq. 3): every tensor that
+ * leaves a ReLU holds unsigned codes 0..255 (saturation at 255), read as such by the next
+ * convolution and by the shortcut; the input quantiser's output, the translation and the head
+ * codes stay signed. Every hidden layer must then carry a ReLU and the last layer none.
  * Constants must satisfy 0 <= M < 2^31, 0 <= shift <= 62, |bias| < 2^30.
  */
 int iodf_init(iodf_ctx** out, const void* model_blob, size_t blob_bytes, int device_ordinal, int max_batch);
