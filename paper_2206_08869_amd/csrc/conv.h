@@ -10,7 +10,7 @@ enum ConvMode : int {
     MODE_ACT = 0,     // write 8-bit codes, pixel-major (NHWC), optionally + shortcut, ReLU
     MODE_COUPLE = 1,  // last layer of t(): state[b-half] += sign * sat8(rq(acc))   (Eq. 1)
     MODE_CODES = 2,   // last layer of a prior head: write int8 codes channel-first
-    MODE_RAW = 3      // store the 32-bit accumulators (no bias, no requantise) to `partial` [npix][n_pad]
+    MODE_RAW = 3      // store the 32-bit accumulators plus bias[] (no requantise) to `partial` [npix][n_pad]
 };
 
 // Second phase of a tap-expanded 3x3 last layer. A 3x3 convolution with few output channels is
@@ -38,8 +38,9 @@ struct ConvArgs {
     //   pos(b, i, j) = b * (h + 2) * (w + 2) + (i + 1) * (w + 2) + (j + 1),
     // plane = bytes between planes (a fixed property of the buffer, >= batch * (h+2) * (w+2) * 64).
     // The 64-byte k-chunks of consecutive pixels are contiguous (whole cache lines per tile load),
-    // a channel concatenation is a range of planes, and the border positions hold zeros that
-    // nobody ever overwrites: they are the convolution's zero padding.
+    // a channel concatenation is a range of planes, and the border positions hold code 0 (byte 0; byte
+    // -128 for tensors of unsigned codes, see out_unsigned) that nobody ever overwrites: they are the
+    // convolution's zero padding.
     const int8_t* in;
     long long in_plane;
     int in_chunk0;
@@ -56,8 +57,8 @@ struct ConvArgs {
     const int32_t* mul;
     const int32_t* shift;  // rq_fast: shift - 32 (every shift of the layer is >= 33); else the shift itself
     int rq_fast;
-    // rq_fast only: smallest accumulator (bias included) whose requantised value reaches 127, saturated
-    // to INT32_MAX; lets a ReLU layer clamp before the multiply instead of after it
+    // rq_fast only: smallest accumulator (bias included) whose requantised value reaches the top code
+    // (127, or 255 with out_unsigned), saturated to INT32_MAX; lets a ReLU layer clamp before the multiply instead of after it
     const int32_t* clamp_hi;
     // Unsigned codes (0..255, stored as code - 128): out_unsigned saturates MODE_ACT results to [0, 255]
     // (the layer then has a ReLU); sc_unsigned says the shortcut bytes are such codes.
