@@ -164,3 +164,28 @@ def test_graph_replay_equals_eager_launches(monkeypatch):
         outs[b] = z.clone()
         assert torch.equal(z, outs[12][:b]) if 12 in outs else True
     eager.close(); graph.close(); big.close()
+
+
+def test_contexts_release_their_device_memory():
+    import torch
+    name = "mini_dense"
+    x = to_gpu(images(name, batch=2))
+    ref = None
+
+    def cycle(n):
+        nonlocal ref
+        for _ in range(n):
+            flow = gpu_flow(name, max_batch=2)
+            z, _ = flow.forward(x)
+            w, _ = flow.encode(x)
+            assert torch.equal(flow.decode(w), x) and torch.equal(flow.inverse(z), x)
+            ref = z.clone() if ref is None else ref
+            assert torch.equal(ref, z)
+            flow.close()
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        return torch.cuda.mem_get_info()[0]
+
+    a = cycle(3)
+    b = cycle(12)
+    assert a - b < (1 << 20), "device memory shrank by %d bytes over 12 contexts" % (a - b)
