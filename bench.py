@@ -138,7 +138,14 @@ def main():
         # a conv kernel's launches arrive split by filter size ("<kernel> 3x3" / "<kernel> 1x1"): list both,
         # and take the roofline over the kernel as a whole (what rocprofv3 reports under one name)
         per_kernel = {}
+        views = {}
         for s in stats:
+            if s["name"].startswith("view:"):      # a second sum over conv launches already listed
+                tops = 2.0 * s["macs"] / (s["total_ms"] * 1e-3) / 1e12
+                views[s["name"][6:]] = dict(launches=s["launches"], total_ms=round(s["total_ms"], 3), tops=round(tops, 2),
+                                            frac_of_int8_peak=round(tops / INT8_PEAK_TOPS, 4),
+                                            share_of_step=round(s["total_ms"] / (1e3 * elapsed), 4))
+                continue
             avg_ms = s["total_ms"] / s["launches"]
             k = dict(name=s["name"], launches=s["launches"], total_ms=round(s["total_ms"], 3),
                      avg_ms=round(avg_ms, 5))
@@ -163,7 +170,8 @@ def main():
                         issued_ops_per_launch=round(2.0 * dom["issued_macs"] / dom["launches"]),
                         launches=dom["launches"], avg_launch_ms=round(dom["total_ms"] / dom["launches"], 5),
                         share_of_step=round(dom["total_ms"] / (1e3 * elapsed), 4),
-                        instrumented_ms_per_step=round(1e3 * prof_elapsed / args.steps, 3))
+                        instrumented_ms_per_step=round(1e3 * prof_elapsed / args.steps, 3),
+                        wide_layers=views)
 
     # compressor leg: iodf_encode = the encode path above + prior masses + rANS containers;
     # iodf_decode = rANS decode interleaved with the inverse flow and the heads

@@ -173,7 +173,8 @@ int iodf_untile_patches(iodf_ctx* ctx, const uint8_t* x_dev, int first_patch, in
  */
 typedef struct iodf_kernel_stat {
     char name[48];      /* kernel, e.g. "k_quant_in"; a conv kernel's launches are listed per filter size:
-                           "conv_igemm<256,256,2,4,4> 3x3" and "conv_igemm<256,256,2,4,4> 1x1" */
+                           "conv_igemm<256,256,2,4,4> 3x3" and "conv_igemm<256,256,2,4,4> 1x1"; entries whose
+                           name starts with "view:" sum conv launches already listed (the wide layers) */
     int64_t launches;
     double total_ms;    /* sum of event-measured durations */
     int64_t macs;       /* algorithmic multiply-accumulates of those launches (kept channels, true widths) */

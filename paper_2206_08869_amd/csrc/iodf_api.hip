@@ -534,7 +534,7 @@ struct iodf_ctx {
     uint32_t* lane_meta = nullptr;     // [max_batch][n_chunks * 16][4]
     unsigned long long* codec_errs = nullptr;  // [3]: clamped residuals, overflowing containers, broken lanes
     // optional per-launch timing (iodf_profile_begin / iodf_profile_end)
-    struct ProfRec { int cls; long long macs, bytes, issued; };
+    struct ProfRec { int cls; long long macs, bytes, issued; int wide; };  // wide: 1 = wide layer, 2 = at level 1 or 2
     bool prof_on = false;
     std::vector<hipEvent_t> prof_ev;
     std::vector<ProfRec> prof_recs;
@@ -553,9 +553,10 @@ bool prof_start(iodf_ctx* ctx, hipStream_t st) {
     return hipEventRecord(ctx->prof_ev[2 * ctx->prof_recs.size()], st) == hipSuccess;
 }
 
-void prof_stop(iodf_ctx* ctx, hipStream_t st, int cls, long long macs, long long bytes, long long issued = 0) {
+void prof_stop(iodf_ctx* ctx, hipStream_t st, int cls, long long macs, long long bytes, long long issued = 0,
+               int wide = 0) {
     (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_recs.size() + 1], st);
-    ctx->prof_recs.push_back({cls, macs, bytes, issued});
+    ctx->prof_recs.push_back({cls, macs, bytes, issued, wide});
 }
 
 // Multiply-accumulates the matrix cores actually run for a conv launch: whole tiles, padded widths.
@@ -633,7 +634,8 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
             HIP_TRY(launch_conv(a, st));
             if (p__)
                 prof_stop(ctx, st, NUM_FLOW_CLS + 2 * conv_pick_tile(a) + (a.taps == 9), L.macs_per_pixel * npix,
-                          (L.bytes_per_pixel + extra) * npix + L.wgt_bytes, issued_macs(a));
+                          (L.bytes_per_pixel + extra) * npix + L.wgt_bytes, issued_macs(a),
+                          L.wide ? (lv <= 2 ? 2 : 1) : 0);
         }
         if (L.mode == MODE_RAW) {
             TapSumArgs t;
@@ -1176,13 +1178,19 @@ int iodf_profile_end(iodf_ctx* ctx, iodf_kernel_stat* stats, int max_stats, int*
     if (!ctx || !stats || !n_stats || max_stats < 1) return IODF_E_ARG;
     if (!ctx->prof_on) return IODF_E_ARG;
     ctx->prof_on = false;
-    // classes: the flow-state passes, then every conv tile split into its 1x1 and 3x3 launches
-    const int ncls = NUM_FLOW_CLS + 2 * conv_num_tiles();
+    // classes: the flow-state passes, then every conv tile split into its 1x1 and 3x3 launches, then
+    // two views over the same conv launches: the wide layers (C_in and C_out >= 128), all of them and
+    // those of levels 1-2 only
+    const int nkern = NUM_FLOW_CLS + 2 * conv_num_tiles();
+    const int ncls = nkern + 2;
     std::vector<iodf_kernel_stat> acc((size_t)ncls);
     for (int c = 0; c < ncls; ++c) {
         memset(&acc[c], 0, sizeof(iodf_kernel_stat));
         if (c < NUM_FLOW_CLS)
             strncpy(acc[c].name, kFlowClsName[c], sizeof(acc[c].name) - 1);
+        else if (c >= nkern)
+            strncpy(acc[c].name, c == nkern ? "view: wide conv layers" : "view: wide conv layers, levels 1-2",
+                    sizeof(acc[c].name) - 1);
         else
             snprintf(acc[c].name, sizeof(acc[c].name), "%s %s", conv_tile_name((c - NUM_FLOW_CLS) / 2),
                      ((c - NUM_FLOW_CLS) & 1) ? "3x3" : "1x1");
@@ -1199,6 +1207,10 @@ int iodf_profile_end(iodf_ctx* ctx, iodf_kernel_stat* stats, int max_stats, int*
         acc[r.cls].total_ms += ms;
         acc[r.cls].macs += r.macs;
         acc[r.cls].issued_macs += r.issued;
+        for (int v = 0; v < r.wide; ++v) {
+            iodf_kernel_stat& w = acc[(size_t)(nkern + v)];
+            w.launches += 1; w.total_ms += ms; w.macs += r.macs; w.bytes += r.bytes; w.issued_macs += r.issued;
+        }
         acc[r.cls].bytes += r.bytes;
     }
     for (hipEvent_t& e : ctx->prof_ev)
