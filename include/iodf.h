@@ -131,8 +131,8 @@ int iodf_inverse(iodf_ctx* ctx, const int32_t* z_dev, int batch, uint8_t* x_dev,
  * Container of one image (little-endian u32 words): total word count; words per (level, lane);
  * final state (low, high) per (level, lane); then each lane's words in decoding order.
  *
- * iodf_prior_cf: z_dev int32 [batch][d], codes_dev int8 [batch][code bytes] (ignored without
- *   heads) -> c_dev, f_dev int32 [batch][d] (device).
+ * iodf_prior_cf: z_dev int32 [batch][d], codes_dev int8 [batch][code bytes] (required when the
+ *   model has heads, ignored otherwise) -> c_dev, f_dev int32 [batch][d] (device).
  * iodf_encode: x_dev uint8 [batch][3][H][W] -> words_dev u32 [batch][cap_words] (one container
  *   per image, never written past cap_words) and sizes_dev u32 [batch] (words each container
  *   needs; larger than cap_words means truncated, see IODF_Q_CODEC_OVERFLOWS).

@@ -1042,7 +1042,7 @@ int iodf_prior_cf(iodf_ctx* ctx, const int32_t* z_dev, const int8_t* codes_dev, 
     if (!ctx) return IODF_E_ARG;
     if (batch < 0 || batch > ctx->max_batch) return IODF_E_BATCH;
     if (batch == 0) return IODF_OK;
-    if (!z_dev || !c_dev || !f_dev) return IODF_E_ARG;
+    if (!z_dev || !c_dev || !f_dev || (ctx->d_codes && !codes_dev)) return IODF_E_ARG;
     hipStream_t st = (hipStream_t)stream;
     HIP_TRY(hipSetDevice(ctx->device));
     const int rc = codec_prepare(ctx);
