@@ -125,7 +125,6 @@ __device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc
             unsigned pk[4];
             static_for<4>([&](auto g_) {
                 constexpr int g = decltype(g_)::value;
-                int y[4];
                 if constexpr (PURE_RELU) {
                     // ReLU without shortcut. The accumulators already hold the bias. Clamping them to
                     // [0, hi] first (hi = the smallest value that requantises to 127; the rescale is
@@ -149,22 +148,52 @@ __device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc
                     pk[g] = a.out_unsigned ? p4 ^ 0x80808080u : p4;  // code u is stored as u - 128
                     return;
                 } else {
-                    int sc = 0;
-                    if (a.shortcut && live) sc = *(const int*)(orow + g * 8 + half * 4);
-                    const int sc_add = (a.shortcut && a.sc_unsigned) ? 128 : 0;  // stored byte = code - 128
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int av = acc[tc][tp][g * 4 + e] + Bq[g][e];
+                    // Signed results: a shortcut and / or no ReLU. The accumulators hold the bias. In
+                    // stored bytes the result is clamp(rq(acc) + shortcut byte, lo, 127): for signed codes
+                    // lo is 0 with a ReLU and -128 without; for unsigned codes (stored as code - 128, which
+                    // only occur here together with a shortcut of the same format) the two offsets of 128
+                    // cancel and ReLU plus saturation to [0, 255] is the clamp to [-128, 127]. The shortcut
+                    // byte is added sign-extended straight out of its dword and the clamp's second half
+                    // drops the byte into the packed dword.
+                    const int sc = (a.shortcut && live) ? *(const int*)(orow + g * 8 + half * 4) : 0;
+                    const int lo2 = (a.relu && !a.out_unsigned) ? 0 : -128;
+                    unsigned p4 = 0;
+                    static_for<4>([&](auto e_) {
+                        constexpr int e = decltype(e_)::value;
+                        const int av = acc[tc][tp][g * 4 + e];
                         const int sgn = av >> 31;
-                        int r = rq_fast_abs((unsigned)((av ^ sgn) - sgn), Mq[g][e], Sq[g][e]);
-                        r = (r ^ sgn) - sgn;
-                        r += (int)(int8_t)(sc >> (8 * e)) + sc_add;
-                        if (a.relu) r = r < 0 ? 0 : r;
-                        y[e] = a.out_unsigned ? (r > 255 ? 255 : r) - 128 : sat8_dev(r);
-                    }
+                        const unsigned q = (__umulhi((unsigned)((av ^ sgn) - sgn), (unsigned)Mq[g][e]) + Rq[g][e]) >> Sq[g][e];
+                        const int r = ((int)q ^ sgn) - sgn;
+                        int t;
+                        if constexpr (e == 0)
+                            asm("v_add_u32_sdwa %0, %1, sext(%2) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD "
+                                "src1_sel:BYTE_0" : "=v"(t) : "v"(r), "v"(sc));
+                        else if constexpr (e == 1)
+                            asm("v_add_u32_sdwa %0, %1, sext(%2) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD "
+                                "src1_sel:BYTE_1" : "=v"(t) : "v"(r), "v"(sc));
+                        else if constexpr (e == 2)
+                            asm("v_add_u32_sdwa %0, %1, sext(%2) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD "
+                                "src1_sel:BYTE_2" : "=v"(t) : "v"(r), "v"(sc));
+                        else
+                            asm("v_add_u32_sdwa %0, %1, sext(%2) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD "
+                                "src1_sel:BYTE_3" : "=v"(t) : "v"(r), "v"(sc));
+                        t = t < lo2 ? lo2 : t;
+                        const int hi2 = 127;
+                        if constexpr (e == 0)
+                            asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:DWORD "
+                                "src1_sel:DWORD" : "+v"(p4) : "v"(t), "v"(hi2));
+                        else if constexpr (e == 1)
+                            asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD "
+                                "src1_sel:DWORD" : "+v"(p4) : "v"(t), "v"(hi2));
+                        else if constexpr (e == 2)
+                            asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD "
+                                "src1_sel:DWORD" : "+v"(p4) : "v"(t), "v"(hi2));
+                        else
+                            asm("v_min_i32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD "
+                                "src1_sel:DWORD" : "+v"(p4) : "v"(t), "v"(hi2));
+                    });
+                    pk[g] = p4;
                 }
-                pk[g] = ((unsigned)y[0] & 0xffu) | (((unsigned)y[1] & 0xffu) << 8) | (((unsigned)y[2] & 0xffu) << 16) |
-                        ((unsigned)y[3] << 24);
             });
             // lower half holds channels {0-3, 8-11, 16-19, 24-27}, upper {4-7, 12-15, 20-23, 28-31}
             auto s01 = __builtin_amdgcn_permlane32_swap(pk[0], pk[1], false, false);
@@ -361,9 +390,9 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
             for (int r = 0; r < 16; ++r) acc[tc][tp][r] = 0;
         });
     });
-    if constexpr (EPI == EPI_FAST_RELU) {
-        // this epilogue clamps before it rescales, so the bias has to be in the accumulators
-        // from the start: register quad g of tile tc holds channels tc*32 + g*8 + half*4 .. +3
+    if constexpr (EPI != EPI_ANY) {
+        // the fast epilogues expect the bias in the accumulators from the start (the ReLU one clamps
+        // before it rescales): register quad g of tile tc holds channels tc*32 + g*8 + half*4 .. +3
         static_for<TC>([&](auto tc_) {
             constexpr int tc = decltype(tc_)::value;
 #pragma unroll
@@ -380,7 +409,7 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, cons
     int* const cst = (int*)(lds + NST * STAGE);  // [3][BC]: bias (or clamp bound), multiplier, shift
     int cb_v = 0, cm_v = 0, cs_v = 0;
     if (tid < BC) {
-        cb_v = EPI == EPI_FAST_RELU ? a.clamp_hi[c0 + tid] : a.bias[c0 + tid];
+        cb_v = EPI == EPI_FAST_RELU ? a.clamp_hi[c0 + tid] : (EPI == EPI_ANY ? a.bias[c0 + tid] : 0);
         cm_v = a.mul[c0 + tid];
         cs_v = a.shift[c0 + tid];
     }
@@ -653,7 +682,11 @@ hipError_t launch_conv(const ConvArgs& a_in, hipStream_t stream) {
     const int npb = (a.npix + t.bp - 1) / t.bp, ncb = a.n_pad / t.bc;
     const int grid = ((npb + 7) / 8) * 8 * ncb;
     const bool fast = a.mode == MODE_ACT && a.rq_fast && a.n_store % 16 == 0;
-    const int epi = !fast ? EPI_ANY : (a.relu && !a.shortcut && a.clamp_hi) ? EPI_FAST_RELU : EPI_FAST;
+    // EPI_FAST covers signed codes, and unsigned ones only where shortcut and result share the format
+    const bool fast_signed_ok = a.shortcut ? a.sc_unsigned == a.out_unsigned : !a.out_unsigned;
+    const int epi = !fast ? EPI_ANY
+                    : (a.relu && !a.shortcut && a.clamp_hi) ? EPI_FAST_RELU
+                    : fast_signed_ok ? EPI_FAST : EPI_ANY;
     const int splits = conv_pick_splits(a, best);
     hipLaunchKernelGGL(t.kern[epi], dim3(grid, splits), dim3(t.threads), t.lds, stream, a, npb, ncb);
     hipError_t e = hipGetLastError();
