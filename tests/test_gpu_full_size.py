@@ -7,7 +7,8 @@ is cut into ragged chunks (other tile positions, other tile tails) or run alone.
 
 IODF_FULL_PARITY=1 in the environment makes the oracle recompute EVERY image of each
 batch instead of the sample (cfg4: about ten minutes of host time).
-IODF_FULL_PARITY_ONLY=cfg4 restricts that to one configuration."""
+IODF_FULL_PARITY_ONLY=cfg4 restricts that to one configuration. IODF_PARITY_128=1 checks the
+first 64 images and 64 seeded ones of a batch (for batches too large to recompute whole)."""
 import os
 
 import numpy as np
@@ -24,6 +25,10 @@ def _sampled(capsys, name, batch, sample, invariance=(), chunk=None):
     full = os.environ.get("IODF_FULL_PARITY") == "1" and os.environ.get("IODF_FULL_PARITY_ONLY", name) == name
     if full:
         sample = tuple(range(batch))
+    elif os.environ.get("IODF_PARITY_128") == "1" and batch > 128 and \
+            os.environ.get("IODF_FULL_PARITY_ONLY", name) == name:
+        rng = np.random.default_rng(2206)
+        sample = tuple(range(64)) + tuple(sorted(int(i) for i in rng.choice(np.arange(64, batch), 64, replace=False)))
 
     def say(*a):
         with capsys.disabled():   # progress lines must reach the terminal while the test runs
