@@ -147,6 +147,9 @@ CONFIGS = {
     # image sides that are not powers of two and not square (levels 12x20 and 6x10)
     "rect_dense": FlowConfig("rect_dense", 24, 40, 3, 2, 2, DENSE, 64, 2, True, seed_id=13),
     "rect_resnet_g": FlowConfig("rect_resnet_g", 24, 40, 2, 2, 2, RESNET, 32, 2, False, keep=0.5, seed_id=14),
+    # six levels down to 1x1 maps: level 6 has 192 input channels per coupling network (whole 64-channel
+    # planes, the first layer stays a 3x3 one) and single-pixel images
+    "deep6": FlowConfig("deep6", 64, 64, 2, 6, 1, PLAIN, 32, 0, True, seed_id=22),
     # The paper's own coupling network (App. B.1): conv_in, 8 residual blocks of two 3x3 convolutions at
     # 128 channels, conv_out; L = 3 levels for 32x32 images, 4 for 64x64, 8 couplings per level; the pruned
     # variant keeps fewer filters the deeper the level (Sec. 5.1, the pruning figure).

@@ -84,7 +84,7 @@ def test_prior_masses_over_the_whole_alphabet_and_all_codes():
 
 
 @pytest.mark.parametrize("name,batch", [("mini_dense", 5), ("mini_dense_g", 4), ("mini_resnet", 3),
-                                         ("odd_dense_g", 3), ("rect_dense", 3), ("mini_paper_g", 3), ("mini_dense_u", 3), ("mini_resnet_gu", 2), ("cfg1", 1), ("cfg2", 64), ("cfg2g", 7)])
+                                         ("odd_dense_g", 3), ("rect_dense", 3), ("mini_paper_g", 3), ("mini_dense_u", 3), ("mini_resnet_gu", 2), ("deep6", 2), ("cfg1", 1), ("cfg2", 64), ("cfg2g", 7)])
 def test_containers_match_oracle_and_decode_everywhere(name, batch):
     import torch
     cfg = CONFIGS[name]

@@ -38,7 +38,7 @@ def _check_full(name, batch=None, kinds=("filtered",), modes=("random",)):
 
 @pytest.mark.parametrize("name", ["cfg1", "mini_resnet", "mini_dense", "mini_dense_g", "mini_resnet_g",
                                   "odd_dense_g", "rect_dense", "rect_resnet_g", "mini_paper_g",
-                                  "mini_dense_u", "mini_resnet_gu", "cfg1_u"])
+                                  "mini_dense_u", "mini_resnet_gu", "cfg1_u", "deep6"])
 def test_small_flows_match_oracle(name):
     _check_full(name, kinds=("filtered", "uniform"))
 
