@@ -40,6 +40,8 @@ def main():
     ap.add_argument("--no-codec", action="store_true", help="skip the compressor leg (flow + prior + rANS)")
     ap.add_argument("--large-image", default="1024x1024",
                     help="HxW of the synthetic high-resolution image of the patch-coding leg ('' to skip)")
+    ap.add_argument("--table1", action="store_true",
+                    help="only time the three isolated 3x3 convolution shapes of the paper's Table 1 and exit")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain 1 GiB device copy (calibrates HBM byte counters) and exit")
     args = ap.parse_args()
@@ -60,6 +62,25 @@ def main():
         return
     import paper_2206_08869_amd as iodf
     from synth import CONFIGS, make_blob, make_images
+
+    if args.table1:
+        # Sec. 4.3, Table 1: 3x3 convolutions on 16x16 maps with (in, out) channels (128,128), (64,256), (32,512);
+        # the paper does not state the batch, so 1 and 32 are timed. Context only: T4 int8 0.0039 / 0.0098 / 0.0131 ms.
+        from synth import prng
+        iodf.load_library()
+        rows = []
+        for c_in, c_out in ((128, 128), (64, 256), (32, 512)):
+            for b in (1, 32):
+                n = b * c_in * 256
+                xq = np.maximum(prng.randint(7, n, -128, 128), 0).astype(np.int8).reshape(b, c_in, 16, 16)
+                wq = prng.randint(8, c_out * c_in * 9, -127, 128).astype(np.int8).reshape(c_out, c_in, 3, 3)
+                y, us = iodf.iodf_conv_probe(xq, wq, np.zeros(c_out, np.int32), np.full(c_out, 1 << 30, np.int32),
+                                             np.full(c_out, 42, np.uint8), relu=True, iters=200)
+                ops = 2.0 * b * 256 * c_in * c_out * 9
+                rows.append(dict(c_in=c_in, c_out=c_out, batch=b, us_per_launch=round(us, 3),
+                                 tops=round(ops / (us * 1e-6) / 1e12, 2)))
+        print(json.dumps({"table1_conv3x3_16x16_int8": rows, "unit": "microseconds per launch (device time, back-to-back)"}))
+        return
 
     cfg = CONFIGS[args.config]
     batch = args.batch or cfg.batch

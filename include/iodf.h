@@ -164,6 +164,20 @@ int iodf_untile_patches(iodf_ctx* ctx, const uint8_t* x_dev, int first_patch, in
                         int img_h, int img_w, void* stream);
 
 /*
+ * One integer-only convolution layer on its own: the isolated shapes the paper times in its
+ * architecture argument (Sec. 4.3, Table 1). All tensors are HOST memory, channel-first:
+ * x int8 [batch][c_in][h][w], w int8 [c_out][c_in][k][k], bias / m int32 [c_out], shift u8 [c_out]
+ * (same constraints as in a blob), y int8 [batch][c_out][h][w] = sat8(relu?(rq(conv(x) + bias))).
+ * The layer is packed and run exactly as inside a flow (same kernels, zero padding (k-1)/2); the
+ * call allocates and frees its own device buffers, runs the layer once for y and then `iters` more
+ * times between two events: *us_per_call (may be NULL) is the mean device time of one launch.
+ * Measurement support, not part of the coding path.
+ */
+int iodf_conv_probe(int device_ordinal, int c_in, int c_out, int k, int h, int w, int batch, int relu,
+                    const int8_t* x_host, const int8_t* w_host, const int32_t* bias_host, const int32_t* m_host,
+                    const uint8_t* shift_host, int8_t* y_host, int iters, float* us_per_call);
+
+/*
  * Per-kernel timing for roofline reports (the paper reports latency only, Sec. 5.2; this is
  * measurement support, not part of the method). Between begin and end every kernel launch of
  * iodf_forward / iodf_inverse is bracketed by HIP events on the caller's stream (no

@@ -23,7 +23,8 @@ IODF_Q_Z_ELEMS, IODF_Q_CODE_BYTES, IODF_Q_WORKSPACE_BYTES, IODF_Q_MACS_FORWARD, 
 
 EXPORTS = ["iodf_init", "iodf_forward", "iodf_inverse", "iodf_query", "iodf_free", "iodf_strerror",
            "iodf_last_hip_error", "iodf_profile_begin", "iodf_profile_end", "iodf_prior_cf", "iodf_encode",
-           "iodf_decode", "iodf_codec_tables", "iodf_tile_patches", "iodf_untile_patches"]
+           "iodf_decode", "iodf_codec_tables", "iodf_tile_patches", "iodf_untile_patches",
+           "iodf_conv_probe"]
 
 
 class KernelStat(ctypes.Structure):
@@ -89,6 +90,9 @@ def load_library(build_if_missing=True):
     L.iodf_decode.argtypes = [vp, vp, ctypes.c_int64, ci, vp, vp]
     L.iodf_codec_tables.restype = ci
     L.iodf_codec_tables.argtypes = [vp, vp]
+    L.iodf_conv_probe.restype = ci
+    L.iodf_conv_probe.argtypes = [ci, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, ci,
+                                  ctypes.POINTER(ctypes.c_float)]
     L.iodf_tile_patches.restype = ci
     L.iodf_tile_patches.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp]
     L.iodf_untile_patches.restype = ci
@@ -144,6 +148,24 @@ def iodf_tile_patches(ctx, img_ptr, img_h, img_w, first_patch, n_patches, x_ptr,
 def iodf_untile_patches(ctx, x_ptr, first_patch, n_patches, img_ptr, img_h, img_w, stream):
     _check(load_library().iodf_untile_patches(ctx, x_ptr, int(first_patch), int(n_patches), img_ptr, int(img_h),
                                               int(img_w), stream))
+
+
+def iodf_conv_probe(x, w, bias, m, shift, relu=True, iters=20, device_ordinal=0):
+    """One conv layer on host arrays: x int8 [B,C_in,h,w], w int8 [C_out,C_in,k,k] -> (y int8 [B,C_out,h,w], us per launch)."""
+    x = np.ascontiguousarray(x, np.int8)
+    w = np.ascontiguousarray(w, np.int8)
+    bias = np.ascontiguousarray(bias, np.int32)
+    m = np.ascontiguousarray(m, np.int32)
+    shift = np.ascontiguousarray(shift, np.uint8)
+    b, c_in, h, wd = x.shape
+    c_out, c_in2, k, k2 = w.shape
+    assert c_in == c_in2 and k == k2 and bias.size == m.size == shift.size == c_out
+    y = np.zeros((b, c_out, h, wd), np.int8)
+    us = ctypes.c_float(0)
+    p = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+    _check(load_library().iodf_conv_probe(int(device_ordinal), c_in, c_out, k, h, wd, b, 1 if relu else 0, p(x), p(w),
+                                          p(bias), p(m), p(shift), p(y), int(iters), ctypes.byref(us)))
+    return y, float(us.value)
 
 
 def iodf_codec_tables():

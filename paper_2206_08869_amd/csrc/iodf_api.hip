@@ -1153,6 +1153,92 @@ int iodf_untile_patches(iodf_ctx* ctx, const uint8_t* x_dev, int first_patch, in
     return IODF_OK;
 }
 
+// One integer-only convolution layer on its own (Sec. 4.3, Table 1 times three such shapes): host
+// tensors in, host tensors out, the same packing and kernels as inside a flow.
+int iodf_conv_probe(int device_ordinal, int c_in, int c_out, int k, int h, int w, int batch, int relu,
+                    const int8_t* x_host, const int8_t* w_host, const int32_t* bias_host, const int32_t* m_host,
+                    const uint8_t* shift_host, int8_t* y_host, int iters, float* us_per_call) {
+    if (c_in < 1 || c_out < 1 || (k != 1 && k != 3) || h < 1 || w < 1 || batch < 1 || c_in > 65536 || c_out > 65536 ||
+        !x_host || !w_host || !bias_host || !m_host || !shift_host || !y_host || iters < 1)
+        return IODF_E_ARG;
+    for (int c = 0; c < c_out; ++c)
+        if (shift_host[c] > 62 || m_host[c] < 0 || bias_host[c] >= (1 << 30) || bias_host[c] <= -(1 << 30)) return IODF_E_ARG;
+    HIP_TRY(hipSetDevice(device_ordinal));
+    HIP_TRY(conv_setup());
+    std::vector<uint8_t> gate((size_t)c_out, 1);
+    HostLayer L{c_out, c_in, k, relu ? 1 : 0, 0, w_host, bias_host, m_host, shift_host, gate.data()};
+    Arena A;
+    DevLayer D{};
+    const int cin_pad = round64(c_in), n_pad = round64(c_out);
+    std::vector<int> rows((size_t)c_out), cols((size_t)c_in);
+    for (int i = 0; i < c_out; ++i) rows[i] = i;
+    for (int i = 0; i < c_in; ++i) cols[i] = i;
+    pack_layer(A, L, rows, cols, cin_pad, D);
+    const long long pp = (long long)(h + 2) * (w + 2);
+    const long long plane = ((long long)batch * pp * 64 + 1023) / 1024 * 1024;
+    if (plane >= (1LL << 31)) return IODF_E_BATCH;
+    const size_t in_bytes = (size_t)plane * (cin_pad / 64), out_bytes = (size_t)plane * (n_pad / 64);
+    // host staging in the library's plane layout (zero borders, zero padding channels)
+    std::vector<int8_t> xin(in_bytes, 0), yout(out_bytes, 0);
+    for (int b = 0; b < batch; ++b)
+        for (int c = 0; c < c_in; ++c)
+            for (int i = 0; i < h; ++i)
+                for (int j = 0; j < w; ++j)
+                    xin[(size_t)(c / 64) * plane + ((size_t)b * pp + (size_t)(i + 1) * (w + 2) + (j + 1)) * 64 + c % 64] =
+                        x_host[(((size_t)b * c_in + c) * h + i) * w + j];
+    uint8_t* params = nullptr;
+    int8_t *din = nullptr, *dout = nullptr;
+    int rc = IODF_OK;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    auto cleanup = [&]() {
+        if (params) (void)hipFree(params);
+        if (din) (void)hipFree(din);
+        if (dout) (void)hipFree(dout);
+        if (e0) (void)hipEventDestroy(e0);
+        if (e1) (void)hipEventDestroy(e1);
+    };
+#define PROBE_TRY(expr)                                                  \
+    do {                                                                 \
+        const hipError_t e__ = (expr);                                   \
+        if (e__ != hipSuccess) { g_last_hip = (int)e__; cleanup(); return IODF_E_HIP; } \
+    } while (0)
+    PROBE_TRY(hipMalloc((void**)&params, A.host.size()));
+    PROBE_TRY(hipMalloc((void**)&din, in_bytes));
+    PROBE_TRY(hipMalloc((void**)&dout, out_bytes));
+    PROBE_TRY(hipMemcpy(params, A.host.data(), A.host.size(), hipMemcpyHostToDevice));
+    PROBE_TRY(hipMemcpy(din, xin.data(), in_bytes, hipMemcpyHostToDevice));
+    PROBE_TRY(hipMemset(dout, 0, out_bytes));
+    ConvArgs a;
+    memset(&a, 0, sizeof(a));
+    a.in = din; a.in_plane = plane; a.cin_pad = cin_pad; a.taps = k * k; a.h = h; a.w = w; a.npix = batch * h * w;
+    a.wgt = (const int8_t*)(params + D.wgt_off); a.n_pad = n_pad;
+    a.bias = (const int32_t*)(params + D.bias_off); a.mul = (const int32_t*)(params + D.mul_off);
+    a.shift = (const int32_t*)(params + D.shift_off); a.rq_fast = D.rq_fast;
+    a.clamp_hi = D.hi_off == (size_t)-1 ? nullptr : (const int32_t*)(params + D.hi_off);
+    a.n_store = n_pad; a.mode = MODE_ACT; a.relu = relu ? 1 : 0; a.out = dout; a.out_plane = plane;
+    PROBE_TRY(hipEventCreate(&e0));
+    PROBE_TRY(hipEventCreate(&e1));
+    PROBE_TRY(launch_conv(a, nullptr));  // warm-up, and the run whose output is returned
+    PROBE_TRY(hipDeviceSynchronize());
+    PROBE_TRY(hipMemcpy(yout.data(), dout, out_bytes, hipMemcpyDeviceToHost));
+    PROBE_TRY(hipEventRecord(e0, nullptr));
+    for (int i = 0; i < iters; ++i) PROBE_TRY(launch_conv(a, nullptr));
+    PROBE_TRY(hipEventRecord(e1, nullptr));
+    PROBE_TRY(hipEventSynchronize(e1));
+    float ms = 0.f;
+    PROBE_TRY(hipEventElapsedTime(&ms, e0, e1));
+#undef PROBE_TRY
+    if (us_per_call) *us_per_call = 1e3f * ms / (float)iters;
+    for (int b = 0; b < batch; ++b)
+        for (int c = 0; c < c_out; ++c)
+            for (int i = 0; i < h; ++i)
+                for (int j = 0; j < w; ++j)
+                    y_host[(((size_t)b * c_out + c) * h + i) * w + j] =
+                        yout[(size_t)(c / 64) * plane + ((size_t)b * pp + (size_t)(i + 1) * (w + 2) + (j + 1)) * 64 + c % 64];
+    cleanup();
+    return rc;
+}
+
 int iodf_profile_begin(iodf_ctx* ctx, int max_launches) {
     if (!ctx || max_launches < 1 || max_launches > (1 << 22)) return IODF_E_ARG;
     if (ctx->prof_on) return IODF_E_ARG;

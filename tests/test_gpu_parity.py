@@ -4,6 +4,7 @@ tolerance anywhere in this file."""
 import numpy as np
 import pytest
 
+import paper_2206_08869_amd as iodf
 from synth import CONFIGS
 from util import blob_of, gpu_flow, images, oracle_model, to_gpu
 
@@ -189,3 +190,25 @@ def test_contexts_release_their_device_memory():
     a = cycle(3)
     b = cycle(12)
     assert a - b < (1 << 20), "device memory shrank by %d bytes over 12 contexts" % (a - b)
+
+
+@pytest.mark.parametrize("c_in,c_out,k,relu,shift_lo", [
+    (128, 128, 3, True, 36), (64, 256, 3, True, 36), (32, 512, 3, True, 36),   # the shapes of Table 1
+    (40, 72, 1, False, 36), (7, 5, 3, False, 20), (130, 64, 3, True, 20),       # ragged widths, short shifts, no ReLU
+])
+def test_single_convolution_matches_oracle(c_in, c_out, k, relu, shift_lo):
+    import oracle
+    rng = np.random.default_rng(c_in * 1000 + c_out)
+    b, h, w = 3, 16, 16
+    x = rng.integers(-128, 128, (b, c_in, h, w)).astype(np.int8)
+    if relu:
+        x = np.maximum(x, 0).astype(np.int8)
+    W = rng.integers(-128, 128, (c_out, c_in, k, k)).astype(np.int8)
+    bias = rng.integers(-5000, 5000, c_out).astype(np.int32)
+    M = rng.integers(1 << 30, (1 << 31) - 1, c_out).astype(np.int32)
+    shift = rng.integers(shift_lo, shift_lo + 6, c_out).astype(np.uint8)
+    y, us = iodf.iodf_conv_probe(x, W, bias, M, shift, relu=relu, iters=3)
+    for i in range(b):
+        ref = oracle.epilogue(oracle.conv_acc(x[i], W, bias), M, shift, relu=relu)
+        assert np.array_equal(y[i], ref), "image %d" % i
+    assert us > 0
