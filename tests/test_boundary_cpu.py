@@ -107,3 +107,7 @@ def test_codec_tables_of_the_library_are_the_correctly_rounded_ones():
     assert lib.iodf_encode(None, None, 1, None, 10, None, None) == -1
     assert lib.iodf_decode(None, None, 10, 1, None, None) == -1
     assert lib.iodf_prior_cf(None, None, None, 1, None, None, None) == -1
+    # the single-layer probe checks its arguments before it touches the device
+    assert lib.iodf_conv_probe(0, 0, 8, 3, 4, 4, 1, 1, None, None, None, None, None, None, 1, None) == -1
+    assert lib.iodf_conv_probe(0, 8, 8, 2, 4, 4, 1, 1, None, None, None, None, None, None, 1, None) == -1
+    assert lib.iodf_tile_patches(None, None, 8, 8, 0, 1, None, None) == -1
