@@ -113,12 +113,16 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # timed region: K steps, nothing else on the stream
+    # timed region: K steps; one event between steps (no synchronisation) gives the per-step spread
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for i in range(args.steps):
+        marks[i].record()
         step()
+    marks[args.steps].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     # the same K steps again with every kernel bracketed by HIP events on the launch stream
     # (per-kernel durations for the roofline; the events add gaps, so this pass is not `value`)
     stats, prof_elapsed = [], None
@@ -292,7 +296,8 @@ def main():
         "metric": "encode-inference images/sec at 3x%dx%d" % (cfg.H, cfg.W) if args.direction == "forward"
         else "decode-inference images/sec at 3x%dx%d" % (cfg.H, cfg.W),
         "value": round(value, 2), "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(ms_per_step, 3), "ms_per_step_median": round(per_step[len(per_step) // 2], 3),
+        "ms_per_step_min_max": [round(per_step[0], 3), round(per_step[-1], 3)], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "%s: %d x 3x%dx%d u8 filtered-noise images, %d levels x %d couplings, %s t() width %d "
                                "depth %d, keep %.2f, prior heads %s, %s activation codes; %s" %
