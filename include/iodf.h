@@ -93,7 +93,10 @@ enum {
  * leaves a ReLU holds unsigned codes 0..255 (saturation at 255), read as such by the next
  * convolution and by the shortcut; the input quantiser's output, the translation and the head
  * codes stay signed. Every hidden layer must then carry a ReLU and the last layer none.
- * Constants must satisfy 0 <= M < 2^31, 0 <= shift <= 62, |bias| < 2^30.
+ * Constants must satisfy 0 <= M < 2^31, 0 <= shift <= 62, |bias| < 2^30, and for every filter
+ * |bias| + X * sum|w| < 2^31 with X = 128 (256 for a layer reading unsigned codes), so that the
+ * 32-bit accumulator of Eq. 4-5 cannot overflow for any input; a blob that breaks one of these is
+ * refused with IODF_E_BLOB.
  */
 int iodf_init(iodf_ctx** out, const void* model_blob, size_t blob_bytes, int device_ordinal, int max_batch);
 

@@ -173,6 +173,21 @@ int check_shapes(const HostModel& m) {
                 if (!L[l].relu) return IODF_E_SHAPE;
             if (L[nl - 1].relu) return IODF_E_SHAPE;
         }
+        // Eq. 4-5 accumulate in 32 bits: refuse a layer whose accumulator could leave int32 for some
+        // input. Input codes are below 128 in magnitude (256 for unsigned codes, whose stored form adds
+        // 128 * sum(w) to the bias); the first layer of a network always reads signed codes.
+        for (int l = 0; l < nl; ++l) {
+            const long long xmax = (m.act_unsigned && l > 0) ? 256 : 128;
+            const long long K = (long long)L[l].C_in * L[l].k * L[l].k;
+            if (K * 127 * xmax + (1LL << 30) < (1LL << 31)) continue;  // cannot overflow whatever the weights
+            for (int c = 0; c < L[l].C_out; ++c) {
+                long long sum = 0;
+                const int8_t* w = L[l].W + (size_t)c * K;
+                for (long long i = 0; i < K; ++i) sum += w[i] < 0 ? -(long long)w[i] : w[i];
+                const long long b = L[l].bias[c] < 0 ? -(long long)L[l].bias[c] : L[l].bias[c];
+                if (sum * xmax + b >= (1LL << 31)) return IODF_E_BLOB;
+            }
+        }
         const int Wd = L[0].C_out;
         if (m.family == FAM_PLAIN) {
             if (nl != 2 || L[1].C_in != Wd) return IODF_E_SHAPE;

@@ -77,6 +77,20 @@ def test_init_rejects_bad_arguments_and_blobs_on_the_host():
         m["act_unsigned"] = 1
         m["nets"][0]["layers"][0]["flags"] &= ~1
     assert _init_code(edited(unsigned_without_relu)) == -3
+    # a filter whose 32-bit accumulator could overflow (Eq. 4-5): 3x3 over 16384 channels, all weights 127
+    def overflowing(m):
+        L0, L1 = m["nets"][0]["layers"]
+        wide = 16384
+        for key in ("bias", "M"):
+            L0[key] = np.resize(L0[key], wide)
+        L0["shift"] = np.resize(L0["shift"], wide); L0["gate"] = np.ones(wide, np.uint8)
+        L0["W"] = np.zeros((wide,) + L0["W"].shape[1:], np.int8)
+        L1["W"] = np.full((L1["W"].shape[0], wide, 3, 3), 127, np.int8)
+    assert _init_code(edited(overflowing)) == -2
+    def wide_but_small(m):
+        overflowing(m)
+        m["nets"][0]["layers"][1]["W"][:] = 1
+    assert _init_code(edited(wide_but_small)) in (0, -5)             # accepted (no GPU here: the HIP error)
     # wrong number of networks for the declared structure
     assert _init_code(edited(lambda m: m["nets"].pop())) == -3
     # wrong wiring: second conv of a plain t() must read the first conv's width
