@@ -323,8 +323,9 @@ __device__ __forceinline__ void wait_tiles_then_barrier() {
 // publishes it and frees the stage consumed before. Activation planes carry a one-pixel zero
 // border per image, so a 3x3 tap is a constant address shift and needs no bounds test; all
 // per-tile address arithmetic is scalar, the per-lane parts are computed once.
+// Four-wave, three-stage configurations are compiled for two workgroups per CU.
 template <int BC, int BP, int WC, int WP, int NST, int EPI>
-__global__ __launch_bounds__(WC* WP * 64) void conv_igemm(const ConvArgs a, const int npb, const int ncb) {
+__global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) void conv_igemm(const ConvArgs a, const int npb, const int ncb) {
     constexpr int NW = WC * WP;
     constexpr int WTC = BC / WC, WTP = BP / WP;  // wave tile
     constexpr int TC = WTC / 32, TP = WTP / 32;  // 32x32 MFMA tiles per wave
@@ -584,8 +585,13 @@ const TileCfg kTiles[] = {
     IODF_TILE(128, 128, 4, 2, 4),
     IODF_TILE(64, 256, 1, 4, 4),
     IODF_TILE(64, 64, 2, 2, 4),
+    // four-wave halves of the first two tiles: 72 KB of LDS and at most 256 registers, so two
+    // workgroups share a CU (see conv_pick_tile)
+    IODF_TILE(256, 128, 2, 2, 3),
+    IODF_TILE(128, 256, 2, 2, 3),
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
+constexpr int kPair256 = 5, kPair128 = 6;  // the two-workgroups-per-CU halves of tiles 0 and 1
 
 int forced_tile() {
     static int v = [] {
@@ -630,19 +636,30 @@ void conv_tile_dims(int tile, int* bc, int* bp) {
     *bp = ok ? kTiles[tile].bp : 0;
 }
 
-// First tile in table order that still fills the chip; otherwise the valid tile with most
-// workgroups, and among equals the one that multiplies the least padding.
+// First tile in table order that still fills the chip (its two-per-CU half when the reduction is
+// short); otherwise the valid tile with most workgroups, and among equals the one that multiplies
+// the least padding.
 int conv_pick_tile(const ConvArgs& a) {
     if (!args_ok(a)) return -1;
     int best = -1;
     long long best_blocks = -1, best_work = 0;
     const int forced = forced_tile();
     if (forced >= 0 && forced < kNumTiles && a.n_pad % kTiles[forced].bc == 0) return forced;
-    for (int i = 0; i < kNumTiles; ++i) {
+    for (int i = 0; i < kPair256; ++i) {
         if (a.n_pad % kTiles[i].bc) continue;
         const long long blocks = (long long)((a.npix + kTiles[i].bp - 1) / kTiles[i].bp) *
                                  ((a.n_store + kTiles[i].bc - 1) / kTiles[i].bc);
-        if (blocks >= 256) return i;
+        if (blocks >= 256) {
+            // Short reductions: the fixed cost of a tile (first loads, epilogue) outweighs its k-loop.
+            // Two half-size workgroups per CU let one's epilogue run under the other's matrix work;
+            // worth it only when the big tile would take more than one round and K is short.
+            const int alt = i == 0 ? kPair256 : i == 1 ? kPair128 : -1;
+            const int nkt = a.taps * (a.cin_pad / KT);
+            const int ncb = a.n_pad / kTiles[i].bc;
+            if (alt >= 0 && blocks > 256 && nkt <= (i == 1 ? 18 : ncb >= 2 ? 16 : 12))
+                return alt;
+            return i;
+        }
         const long long work = blocks * kTiles[i].bc * kTiles[i].bp;
         if (blocks > best_blocks || (blocks == best_blocks && work < best_work)) {
             best_blocks = blocks;
