@@ -57,7 +57,7 @@ def test_cfg2_full_batch_matches_oracle():
     _check_full("cfg2")
 
 
-def test_cfg2_gated_scatter_add_matches_oracle():
+def test_cfg2_gated_residual_matches_oracle():
     _check_full("cfg2g")
 
 
