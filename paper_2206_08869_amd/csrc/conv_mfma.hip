@@ -100,6 +100,42 @@ __device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc
         m = m < a.npix ? m : 0;
         ppos[tp] = (long long)bordered_pos(a, m, hw, W2, PP) * 64;
     }
+    // Shortcut codes (Eq. 2) sit where the result goes. Each lane fetches, with one 16-byte load per
+    // 32x32 tile, exactly the 16 bytes it will store (all of them before the first store), and the
+    // store's three permlane rounds run backwards to bring them into the accumulators' quad layout:
+    // v_permlane32_swap undoes itself.
+    [[maybe_unused]] v4i scq[TC][TP];
+    if constexpr (!PURE_RELU) {
+        static_for<TC>([&](auto tc_) {
+            constexpr int tc = decltype(tc_)::value;
+            static_for<TP>([&](auto tp_) {
+                constexpr int tp = decltype(tp_)::value;
+                v4i s4 = {0, 0, 0, 0};
+                if (a.shortcut) {
+                    const int ch0 = ch_base + tc * 32;
+                    const bool ok = pix_base + tp * 32 + l32 < a.npix && ch0 + half * 16 < a.n_store;
+                    const int8_t* srow =
+                        a.out + (long long)(a.out_chunk0 + (ch0 >> 6)) * a.out_plane + ppos[tp] + (ch0 & 63);
+                    if (ok) s4 = *(const v4i*)(srow + half * 16);
+                }
+                scq[tc][tp] = s4;
+            });
+        });
+        if (a.shortcut) {
+            static_for<TC>([&](auto tc_) {
+                constexpr int tc = decltype(tc_)::value;
+                static_for<TP>([&](auto tp_) {
+                    constexpr int tp = decltype(tp_)::value;
+                    const v4i s4 = scq[tc][tp];  // {x0, w0, x1, w1} of the store below
+                    auto x = __builtin_amdgcn_permlane32_swap((unsigned)s4[0], (unsigned)s4[2], false, false);
+                    auto w = __builtin_amdgcn_permlane32_swap((unsigned)s4[1], (unsigned)s4[3], false, false);
+                    auto q01 = __builtin_amdgcn_permlane32_swap(x[0], w[0], false, false);
+                    auto q23 = __builtin_amdgcn_permlane32_swap(x[1], w[1], false, false);
+                    scq[tc][tp] = v4i{(int)q01[0], (int)q01[1], (int)q23[0], (int)q23[1]};
+                });
+            });
+        }
+    }
     static_for<TC>([&](auto tc_) {
         constexpr int tc = decltype(tc_)::value;
         // bias (PURE_RELU: the clamp bound instead), multiplier, shift - 32 of this lane's 16 channels
@@ -155,7 +191,7 @@ __device__ __forceinline__ void conv_epilogue_fast(const ConvArgs& a, v16i (&acc
                     // cancel and ReLU plus saturation to [0, 255] is the clamp to [-128, 127]. The shortcut
                     // byte is added sign-extended straight out of its dword and the clamp's second half
                     // drops the byte into the packed dword.
-                    const int sc = (a.shortcut && live) ? *(const int*)(orow + g * 8 + half * 4) : 0;
+                    const int sc = scq[tc][tp][g];
                     const int lo2 = (a.relu && !a.out_unsigned) ? 0 : -128;
                     unsigned p4 = 0;
                     static_for<4>([&](auto e_) {
