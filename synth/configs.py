@@ -144,8 +144,9 @@ CONFIGS = {
     "mini_resnet_g": FlowConfig("mini_resnet_g", 16, 16, 3, 2, 2, RESNET, 32, 2, False, keep=0.5, seed_id=10),
     "mid_dense": FlowConfig("mid_dense", 32, 32, 3, 3, 2, DENSE, 256, 4, True, seed_id=11),
     "odd_dense_g": FlowConfig("odd_dense_g", 16, 16, 2, 2, 2, DENSE, 72, 2, True, keep=0.625, seed_id=12),
-    # image sides that are not powers of two and not square (levels 12x20 and 6x10)
-    "rect_dense": FlowConfig("rect_dense", 24, 40, 3, 2, 2, DENSE, 64, 2, True, seed_id=13),
+    # image sides that are not powers of two and not square (levels 12x20 and 6x10); depth 3 gives the last
+    # layer 256 input channels, the width from which the library tap-expands it
+    "rect_dense": FlowConfig("rect_dense", 24, 40, 3, 2, 2, DENSE, 64, 3, True, seed_id=13),
     "rect_resnet_g": FlowConfig("rect_resnet_g", 24, 40, 2, 2, 2, RESNET, 32, 2, False, keep=0.5, seed_id=14),
     # six levels down to 1x1 maps: level 6 has 192 input channels per coupling network (whole 64-channel
     # planes, the first layer stays a 3x3 one) and single-pixel images
