@@ -526,8 +526,13 @@ struct iodf_ctx {
     std::vector<long long> plane;                   // bytes between 64-channel planes = max_batch * (h+2)*(w+2) * 64
     std::vector<int32_t*> state;      // per level (1-based), int32 [B][h][w][C]
     unsigned long long* range_errs = nullptr;
-    int32_t* partial = nullptr;       // split-K scratch of the last layers (zero between launches)
+    // Scratch of the last layers, int32 [npix][n_pad]. Two buffers because their users disagree about its
+    // state: a tap-expanded layer overwrites `raw` and leaves its maps there, a split-K layer adds into
+    // `partial`, which its finishing pass leaves all zero again.
+    int32_t* partial = nullptr;
     size_t partial_elems = 0;
+    int32_t* raw = nullptr;
+    size_t raw_elems = 0;
     size_t workspace_bytes = 0;
     long long macs_fwd = 0, macs_inv = 0, macs_wide = 0;
     int conv_launches = 0;
@@ -628,7 +633,11 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
         a.out_unsigned = L.out_unsigned && L.mode == MODE_ACT;
         a.sc_unsigned = L.sc_unsigned;
         a.clamp_hi = L.hi_off == (size_t)-1 ? nullptr : (const int32_t*)(ctx->params + L.hi_off);
-        if (L.mode != MODE_ACT && (size_t)npix * L.n_pad <= ctx->partial_elems) a.partial = ctx->partial;
+        if (L.mode == MODE_RAW) {
+            if ((size_t)npix * L.n_pad <= ctx->raw_elems) a.partial = ctx->raw;
+        } else if (L.mode != MODE_ACT && (size_t)npix * L.n_pad <= ctx->partial_elems) {
+            a.partial = ctx->partial;
+        }
         a.mode = L.mode;
         a.relu = L.relu;
         if (L.mode == MODE_ACT) {
@@ -678,7 +687,7 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
     return IODF_OK;
 }
 
-static const int32_t* partial_of(const iodf_ctx* ctx) { return ctx->partial; }
+static const int32_t* partial_of(const iodf_ctx* ctx) { return ctx->raw; }
 
 }  // namespace
 
@@ -835,14 +844,16 @@ int iodf_init(iodf_ctx** out, const void* model_blob, size_t blob_bytes, int dev
             if (e != hipSuccess) { g_last_hip = (int)e; ok = false; }
         }
     }
-    // split-K scratch: enough for the last layer of any network at full batch
+    // last-layer scratch: enough for any network at full batch
     for (const DevNet& N : ctx->nets) {
         const size_t px = (size_t)max_batch * (hm.H >> N.level) * (hm.W >> N.level);
-        ctx->partial_elems = std::max(ctx->partial_elems, px * (size_t)N.layers.back().n_pad);
+        size_t& elems = N.layers.back().mode == MODE_RAW ? ctx->raw_elems : ctx->partial_elems;
+        elems = std::max(elems, px * (size_t)N.layers.back().n_pad);
     }
     ok = ok && dev_alloc((void**)&ctx->partial, 4 * ctx->partial_elems);
+    ok = ok && dev_alloc((void**)&ctx->raw, 4 * ctx->raw_elems);
     if (ok) {
-        e = hipMemset(ctx->partial, 0, 4 * ctx->partial_elems);
+        e = hipMemset(ctx->partial, 0, std::max<size_t>(4 * ctx->partial_elems, 256));
         if (e != hipSuccess) { g_last_hip = (int)e; ok = false; }
     }
     if (ok) {
@@ -878,6 +889,7 @@ void iodf_free(iodf_ctx* ctx) {
     if (ctx->stage_z) (void)hipFree(ctx->stage_z);
     if (ctx->stage_codes) (void)hipFree(ctx->stage_codes);
     if (ctx->partial) (void)hipFree(ctx->partial);
+    if (ctx->raw) (void)hipFree(ctx->raw);
     for (hipEvent_t& e : ctx->prof_ev)
         if (e) (void)hipEventDestroy(e);
     delete ctx;

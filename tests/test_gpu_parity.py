@@ -49,6 +49,35 @@ def test_degenerate_networks_match_oracle(name):
     _check_full(name, modes=("zero", "bias_only"))
 
 
+def test_expanded_and_split_k_last_layers_in_one_model():
+    """One model whose networks end differently: 3x3 over 2304 channels (tap-expanded, leaves its raw
+    maps in the scratch) and 1x1 over 2304 channels on a few pixels (split over K, needs a zeroed
+    scratch). The two must not share the buffer."""
+    import oracle
+    import torch
+    from synth import make_blob, make_images
+    from synth.configs import DENSE, FlowConfig
+    from synth.model import pack_blob, parse_blob
+    cfg = FlowConfig("mix_last", 16, 16, 2, 2, 2, DENSE, 256, 8, False, seed_id=31)
+    m = parse_blob(make_blob(cfg).copy())
+    for n in (1, 3):   # second coupling of each level: keep the centre tap only
+        L = m["nets"][n]["layers"][-1]
+        L["W"] = np.ascontiguousarray(L["W"][:, :, 1:2, 1:2])
+    blob = pack_blob(m)
+    x = make_images(cfg)
+    om = oracle.Model(blob)
+    z_ref, _ = om.forward(x)
+    flow = iodf.Flow(blob, max_batch=cfg.batch, device=0)
+    for _rep in range(2):   # the second pass starts from whatever the first left in the scratch
+        z, _ = flow.forward(to_gpu(x))
+        torch.cuda.synchronize()
+        assert np.array_equal(z.cpu().numpy(), z_ref)
+        x2 = flow.inverse(z)
+        torch.cuda.synchronize()
+        assert np.array_equal(x2.cpu().numpy(), x)
+    flow.close()
+
+
 def test_mid_dense_matches_oracle():
     _check_full("mid_dense", batch=5)   # 5*256 pixels at level 1: ragged against every pixel tile
 
