@@ -226,9 +226,22 @@ def test_contexts_release_their_device_memory():
     (40, 72, 1, False, 36), (7, 5, 3, False, 20), (130, 64, 3, True, 20),       # ragged widths, short shifts, no ReLU
 ])
 def test_single_convolution_matches_oracle(c_in, c_out, k, relu, shift_lo):
+    _check_single_convolution(c_in, c_out, k, relu, shift_lo, 3, 16, 16)
+
+
+@pytest.mark.parametrize("c_in,c_out,k,b", [
+    (512, 512, 1, 80),    # 640 tiles of 256x256 and 8 k-tiles: the 256x128 half tile, two workgroups per CU
+    (128, 128, 3, 160),   # 320 tiles of 128x512 and 18 k-tiles: the 128x256 half tile
+    (1024, 512, 1, 72),   # 576 tiles, 16 k-tiles: the last reduction length that takes the half tile
+    (1088, 512, 1, 72),   # 17 k-tiles: back on the 256x256 tile
+])
+def test_single_convolution_on_many_pixels_matches_oracle(c_in, c_out, k, b):
+    _check_single_convolution(c_in, c_out, k, True, 36, b, 32, 32)
+
+
+def _check_single_convolution(c_in, c_out, k, relu, shift_lo, b, h, w):
     import oracle
     rng = np.random.default_rng(c_in * 1000 + c_out)
-    b, h, w = 3, 16, 16
     x = rng.integers(-128, 128, (b, c_in, h, w)).astype(np.int8)
     if relu:
         x = np.maximum(x, 0).astype(np.int8)
