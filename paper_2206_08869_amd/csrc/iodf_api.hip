@@ -609,7 +609,6 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
     const int h = ctx->shape.H >> lv, w = ctx->shape.W >> lv;
     const int npix = batch * h * w;
     const int32_t* phi = (const int32_t*)(ctx->params + N.phi_off);
-    const int ntile = conv_num_tiles();
     const long long plane = ctx->plane[lv];
     PROF_LAUNCH(ctx, st, CLS_QUANT_IN, 0, (long long)npix * (4 * N.C_in + N.cin_pad0),
                 launch_quant_in(ctx->state[lv], npix, h, w, N.C, phi, N.C_in, N.M_in, N.s_in, ctx->buf[lv][BUF_XQ],
@@ -898,7 +897,6 @@ void iodf_free(iodf_ctx* ctx) {
 static int enqueue_forward(iodf_ctx* ctx, const uint8_t* x_dev, int batch, int32_t* z_dev, int8_t* codes_dev,
                            hipStream_t st) {
     const HostModel& m = ctx->shape;
-    const int ntile = conv_num_tiles();
     PROF_LAUNCH(ctx, st, CLS_INGEST, 0, 5LL * batch * ctx->d,
                 launch_ingest_squeeze(x_dev, batch, m.H, m.W, ctx->state[1], st));
     for (int lv = 1; lv <= m.levels; ++lv) {
