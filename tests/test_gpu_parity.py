@@ -229,14 +229,16 @@ def test_single_convolution_matches_oracle(c_in, c_out, k, relu, shift_lo):
     _check_single_convolution(c_in, c_out, k, relu, shift_lo, 3, 16, 16)
 
 
-@pytest.mark.parametrize("c_in,c_out,k,b", [
-    (512, 512, 1, 80),    # 640 tiles of 256x256 and 8 k-tiles: the 256x128 half tile, two workgroups per CU
-    (128, 128, 3, 160),   # 320 tiles of 128x512 and 18 k-tiles: the 128x256 half tile
-    (1024, 512, 1, 72),   # 576 tiles, 16 k-tiles: the last reduction length that takes the half tile
-    (1088, 512, 1, 72),   # 17 k-tiles: back on the 256x256 tile
+@pytest.mark.parametrize("c_in,c_out,k,b,side", [
+    (512, 512, 1, 80, 32),    # 640 tiles of 256x256 and 8 k-tiles: the 256x128 half tile, two workgroups per CU
+    (128, 128, 3, 160, 32),   # 320 tiles of 128x512 and 18 k-tiles: the 128x256 half tile
+    (1024, 512, 1, 72, 32),   # 576 tiles, 16 k-tiles: the last reduction length that takes the half tile
+    (1088, 512, 1, 72, 32),   # 17 k-tiles: back on the 256x256 tile
+    (512, 512, 1, 92, 30),    # 82800 pixels: a ragged last half tile, image sides that are no powers of two
+    (128, 128, 3, 183, 30),   # 164700 pixels, ragged, 3x3
 ])
-def test_single_convolution_on_many_pixels_matches_oracle(c_in, c_out, k, b):
-    _check_single_convolution(c_in, c_out, k, True, 36, b, 32, 32)
+def test_single_convolution_on_many_pixels_matches_oracle(c_in, c_out, k, b, side):
+    _check_single_convolution(c_in, c_out, k, True, 36, b, side, side)
 
 
 def _check_single_convolution(c_in, c_out, k, relu, shift_lo, b, h, w):
