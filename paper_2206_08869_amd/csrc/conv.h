@@ -86,8 +86,9 @@ struct ConvArgs {
 
 // Enqueue the layer on `stream`. Returns hipSuccess or the launch error.
 hipError_t launch_conv(const ConvArgs& a, hipStream_t stream);
-// Index of the tile configuration launch_conv picks for `a` (-1: invalid arguments),
-// the number of configurations, and a printable name ("conv_igemm<256,256,2,2>").
+// Index of the kernel configuration launch_conv picks for `a` (-1: invalid arguments; the last index
+// stands for the persistent form of the first tile), the number of configurations, and a printable
+// name ("conv_igemm<256,256,2,4,4>").
 int conv_pick_tile(const ConvArgs& a);
 int conv_num_tiles();
 const char* conv_tile_name(int tile);

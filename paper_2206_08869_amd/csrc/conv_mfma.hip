@@ -566,6 +566,214 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
         conv_epilogue<TC, TP>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw);
 }
 
+// Persistent form of conv_igemm for launches with several output tiles per CU (fast epilogues only,
+// no split-K, a k-tile count that is a multiple of NST). One workgroup per CU walks the tiles
+// blockIdx.x, blockIdx.x + gridDim.x, ... The stream of k-tiles runs on across output tiles: once
+// the last k-tile of a tile has been issued the load pointers move to the workgroup's next tile, so
+// the loads that conv_igemm spends on dead stages at the end of its k loop fetch the first k-tiles
+// of the next output tile here, and these land while the epilogue runs. Loads and stores retire in
+// order on one counter: at the start of a tile "at most (NST - 2) * LPT outstanding" still means
+// that its k-tile 0 has landed (the epilogue's stores are younger), and the wait never asks for
+// the stores themselves beyond that. Per-channel constants, the bias included, take the same road
+// as the tiles: four 1 KB loads straight into one of two LDS buffers, issued right behind the last
+// k-tile of the previous output tile, so they too are older than the next tile's k-tile 0.
+template <int BC, int BP, int WC, int WP, int NST, int EPI>
+__global__ __launch_bounds__(WC* WP * 64) void conv_igemm_persist(const ConvArgs a, const int npb, const int ncb) {
+    static_assert(EPI != EPI_ANY, "fast epilogues only");
+    static_assert(BC == 256 && WC * WP >= 4, "one wave-wide load per constant array");
+    constexpr int NW = WC * WP;
+    constexpr int WTC = BC / WC, WTP = BP / WP;
+    constexpr int TC = WTC / 32, TP = WTP / 32;
+    constexpr int WI = BC / 16 / NW, AI = BP / 16 / NW;
+    constexpr int LPT = WI + AI;
+    constexpr int STAGE = (BC + BP) * KT;
+    static_assert(NST >= 3 && (NST - 2) * LPT < 64, "pipeline depth must fit the vmcnt counter");
+
+    extern __shared__ __align__(1024) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wc = wave % WC, wp = wave / WC;
+    const int nkt = a.taps * (a.cin_pad / KT);  // a multiple of NST (the launcher checks)
+    const long long wtile = (long long)a.n_pad * KT;
+    const int hw = a.h * a.w;
+    const int W2 = a.w + 2, PP = (a.h + 2) * W2;
+
+    // Tiles are numbered by slot as in conv_igemm (slot & 7 = XCD, whole pixel blocks per XCD);
+    // gridDim.x is a multiple of 8, so a workgroup's slots stay on its XCD.
+    const int nslots = ((npb + 7) / 8) * 8 * ncb;
+    auto slot_tile = [&](int s, int& p0, int& c0) {
+        const int xcd = s & 7, q = s >> 3;
+        const int pb = (q / ncb) * 8 + xcd, cb = q % ncb;
+        p0 = pb * BP;
+        c0 = cb * BC;
+        return pb < npb && c0 < a.n_store;
+    };
+    auto next_slot = [&](int s) {
+        int p, c;
+        while (s < nslots && !slot_tile(s, p, c)) s += (int)gridDim.x;
+        return s;
+    };
+    int cur = next_slot((int)blockIdx.x);
+    if (cur >= nslots) return;
+
+    const int lrow = lane >> 2;
+    const int lpart = (lane & 3) ^ ((lane >> 4) & 3);
+    const unsigned woffl = (unsigned)(lrow * KT + lpart * 16);
+    const long long next_plane = a.in_plane - (a.taps == 9 ? (long long)(2 * W2 + 2) * KT : 0LL);
+    const int8_t* const abase = a.in + (long long)a.in_chunk0 * a.in_plane;
+
+    typedef const void __attribute__((address_space(1))) * gptr_t;
+    typedef void __attribute__((address_space(3))) * lptr_t;
+    unsigned aoffl[AI];
+    const int8_t* wt;
+    const int8_t* at;
+    int itile, itap, ikx;
+    int gi = 0;            // k-tiles issued so far: stage = gi % NST
+    int ld_slot, nx_slot;  // slot being loaded, next slot to load
+    auto load_setup = [&](int s) {
+        int p0, c0;
+        slot_tile(s, p0, c0);
+#pragma unroll
+        for (int u = 0; u < AI; ++u) {
+            int m = p0 + (wave * AI + u) * 16 + lrow;
+            m = m < a.npix ? m : a.npix - 1;
+            aoffl[u] = (unsigned)bordered_pos(a, m, hw, W2, PP) * KT + (unsigned)(lpart * 16);
+        }
+        itile = 0;
+        itap = 0;
+        ikx = 0;
+        wt = a.wgt + (long long)(c0 + wave * WI * 16) * KT;
+        at = abase + (a.taps == 9 ? (long long)(-W2 - 1) * KT : 0LL);  // tap (0, 0) reads pixel (i - 1, j - 1)
+        ld_slot = s;
+    };
+    auto uniform = [](const int8_t* p) {
+        const unsigned long long v = (unsigned long long)p;
+        const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+        const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+        return (const int8_t*)(((unsigned long long)hi << 32) | lo);
+    };
+    // [2][4][BC] behind the ring: clamp bound (ReLU epilogue), multiplier, shift, bias of the channels of
+    // the tile being computed and of the next one; wave w < 4 fetches array w
+    int* const cstbuf = (int*)(lds + NST * STAGE);
+    int ctile = 0;  // output tiles whose constants have been requested
+    auto load_consts = [&](int s) {
+        int p0, c0;
+        slot_tile(s, p0, c0);
+        if (wave < 4) {
+            const int32_t* arr = wave == 0 ? (EPI == EPI_FAST_RELU ? a.clamp_hi : a.mul) : wave == 1 ? a.mul : wave == 2 ? a.shift : a.bias;
+            const int8_t* src = uniform((const int8_t*)(arr + c0));
+            __builtin_amdgcn_global_load_lds((gptr_t)(src + lane * 16), (lptr_t)(cstbuf + ((ctile & 1) * 4 + wave) * BC), 16, 0, 0);
+        }
+        ++ctile;
+    };
+    auto issue = [&]() {
+        unsigned char* sb = lds + (gi % NST) * STAGE;
+        const int8_t* wu = uniform(wt);
+        const int8_t* au = uniform(at);
+#pragma unroll
+        for (int u = 0; u < WI; ++u)
+            __builtin_amdgcn_global_load_lds((gptr_t)(wu + u * 1024 + woffl), (lptr_t)(sb + (wave * WI + u) * 1024), 16,
+                                             0, 0);
+#pragma unroll
+        for (int u = 0; u < AI; ++u)
+            __builtin_amdgcn_global_load_lds((gptr_t)(au + aoffl[u]), (lptr_t)(sb + BC * KT + (wave * AI + u) * 1024),
+                                             16, 0, 0);
+        ++gi;
+        if (++itile == nkt) {
+            // once per output tile: on to this workgroup's next slot; after the last one the same tile
+            // is loaded again into stages nobody reads, which keeps the loads per step constant
+            const int s = nx_slot < nslots ? nx_slot : ld_slot;
+            if (nx_slot < nslots) nx_slot = next_slot(nx_slot + (int)gridDim.x);
+            load_setup(s);
+            load_consts(s);
+        } else {
+            const bool wrap = itap + 1 == a.taps;
+            const bool row = ikx == 2;
+            wt += wtile;
+            at += wrap ? next_plane : (long long)((row ? W2 - 2 : 1) * KT);
+            itap = wrap ? 0 : itap + 1;
+            ikx = (wrap || row) ? 0 : ikx + 1;
+        }
+    };
+    load_setup(cur);
+    load_consts(cur);
+    nx_slot = next_slot(cur + (int)gridDim.x);
+
+    const int half = lane >> 5, l32 = lane & 31;
+    const int sw = (l32 >> 2) & 3;
+    const int off0 = (half ^ sw) * 16;
+    const int wl0 = (wc * WTC + l32) * KT, al0 = BC * KT + (wp * WTP + l32) * KT;
+    v16i acc[TC][TP];
+    v4i wf0[TC], af0[TP], wf1[TC], af1[TP];
+    auto read_frags = [&](int stage, int ks, v4i (&wf)[TC], v4i (&af)[TP]) {
+        const unsigned char* sb = lds + stage * STAGE;
+        const int off = off0 ^ (ks * 32);
+#pragma unroll
+        for (int tc = 0; tc < TC; ++tc) wf[tc] = *(const v4i*)(sb + wl0 + tc * 32 * KT + off);
+#pragma unroll
+        for (int tp = 0; tp < TP; ++tp) af[tp] = *(const v4i*)(sb + al0 + tp * 32 * KT + off);
+    };
+    auto mma = [&](v4i (&wf)[TC], v4i (&af)[TP]) {
+        static_for<TC>([&](auto tc_) {
+            constexpr int tc = decltype(tc_)::value;
+            static_for<TP>([&](auto tp_) {
+                constexpr int tp = decltype(tp_)::value;
+                acc[tc][tp] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[tc], af[tp], acc[tc][tp], 0, 0, 0);
+            });
+        });
+    };
+    auto step = [&](auto st_) {
+        constexpr int st = decltype(st_)::value;
+        read_frags(st, 1, wf1, af1);
+        mma(wf0, af0);
+        issue();
+        wait_tiles_then_barrier<(NST - 2) * LPT>();
+        read_frags((st + 1) % NST, 0, wf0, af0);
+        mma(wf1, af1);
+    };
+
+#pragma unroll
+    for (int t = 0; t < NST - 1; ++t) issue();
+    for (int n = 0;; ++n) {
+        int p0, c0;
+        slot_tile(cur, p0, c0);
+        int* const cst = cstbuf + (n & 1) * 4 * BC;
+        // k-tile 0 of this output tile and, before it, its constants have landed (first tile: just
+        // issued; later tiles: issued during the previous k loop)
+        wait_tiles_then_barrier<(NST - 2) * LPT>();
+        // accumulators start at the bias (the fast epilogues expect it there)
+        static_for<TC>([&](auto tc_) {
+            constexpr int tc = decltype(tc_)::value;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const v4i b4 = *(const v4i*)(cst + 3 * BC + wc * WTC + tc * 32 + g * 8 + half * 4);
+                static_for<TP>([&](auto tp_) {
+                    constexpr int tp = decltype(tp_)::value;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[tc][tp][g * 4 + e] = b4[e];
+                });
+            }
+        });
+        read_frags(0, 0, wf0, af0);
+        for (int kt = 0; kt < nkt; kt += NST) {
+            step(std::integral_constant<int, 0>{});
+            step(std::integral_constant<int, 1>{});
+            step(std::integral_constant<int, 2>{});
+            if constexpr (NST > 3) step(std::integral_constant<int, 3>{});
+            static_assert(NST <= 4, "unrolled for at most four stages");
+        }
+        const int nxt = next_slot(cur + (int)gridDim.x);
+        if constexpr (EPI == EPI_FAST_RELU)
+            conv_epilogue_fast<TC, TP, true>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw, cst, BC, wc * WTC);
+        else
+            conv_epilogue_fast<TC, TP, false>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw, cst, BC, wc * WTC);
+        if (nxt >= nslots) break;
+        cur = nxt;
+    }
+    // drain the tail loads (they target stages nobody reads any more) before the wave retires
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
 // Second phase of a split-K layer: requantise the summed accumulators, apply the layer's
 // mode, and leave the scratch zeroed for the next user. One thread per (pixel, channel).
 __global__ void conv_splitk_finish(const ConvArgs a) {
@@ -629,6 +837,13 @@ const TileCfg kTiles[] = {
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 constexpr int kPair256 = 5, kPair128 = 6;  // the two-workgroups-per-CU halves of tiles 0 and 1
 
+// Persistent form of tile 0 (see conv_igemm_persist), by fast epilogue, and its LDS bytes.
+void (*const kPersist[3])(const ConvArgs, int, int) = {nullptr, conv_igemm_persist<256, 256, 2, 4, 4, EPI_FAST>,
+                                                        conv_igemm_persist<256, 256, 2, 4, 4, EPI_FAST_RELU>};
+constexpr size_t kPersistLds = (size_t)4 * (256 + 256) * KT + 2 * 4 * 256 * sizeof(int);
+int g_persist_grid = 0;  // workgroups of a persistent launch: one per CU, a multiple of 8 (set by conv_setup)
+constexpr int kPersistTile = kNumTiles;  // what conv_pick_tile answers for a persistent launch of tile 0
+
 int forced_tile() {
     static int v = [] {
         const char* e = getenv("IODF_TILE");
@@ -661,15 +876,46 @@ hipError_t conv_setup() {
             if (e != hipSuccess) return e;
         }
     }
+    for (int v = 1; v < 3; ++v) {
+        hipError_t e = hipFuncSetAttribute((const void*)kPersist[v], hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)kPersistLds);
+        if (e != hipSuccess) return e;
+    }
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    g_persist_grid = cus / 8 * 8;
     return hipSuccess;
 }
 
-int conv_num_tiles() { return kNumTiles; }
-const char* conv_tile_name(int tile) { return tile >= 0 && tile < kNumTiles ? kTiles[tile].name : "?"; }
+int conv_num_tiles() { return kNumTiles + 1; }
+const char* conv_tile_name(int tile) {
+    if (tile == kPersistTile) return "conv_igemm_persist<256,256,2,4,4>";
+    return tile >= 0 && tile < kNumTiles ? kTiles[tile].name : "?";
+}
 void conv_tile_dims(int tile, int* bc, int* bp) {
+    if (tile == kPersistTile) tile = 0;
     const bool ok = tile >= 0 && tile < kNumTiles;
     *bc = ok ? kTiles[tile].bc : 0;
     *bp = ok ? kTiles[tile].bp : 0;
+}
+
+int conv_pick_splits(const ConvArgs& a, int tile);
+
+// Epilogue variant a layer runs with.
+int pick_epi(const ConvArgs& a) {
+    const bool fast = a.mode == MODE_ACT && a.rq_fast && a.n_store % 16 == 0;
+    // EPI_FAST covers signed codes, and unsigned ones only where shortcut and result share the format
+    const bool fast_signed_ok = a.shortcut ? a.sc_unsigned == a.out_unsigned : !a.out_unsigned;
+    return !fast ? EPI_ANY : (a.relu && !a.shortcut && a.clamp_hi) ? EPI_FAST_RELU : fast_signed_ok ? EPI_FAST : EPI_ANY;
+}
+
+// Whether the 256x256 tile runs in its persistent form: three or more tiles per CU, a fast epilogue
+// and whole rounds of the stage ring (with two tiles per CU the plain kernel was as fast or faster).
+bool persist_ok(const ConvArgs& a, long long tiles) {
+    const int nkt = a.taps * (a.cin_pad / KT);
+    return pick_epi(a) != EPI_ANY && nkt % 4 == 0 && g_persist_grid >= 8 && tiles >= 3LL * g_persist_grid;
 }
 
 // First tile in table order that still fills the chip (its two-per-CU half when the reduction is
@@ -688,12 +934,13 @@ int conv_pick_tile(const ConvArgs& a) {
         if (blocks >= 256) {
             // Short reductions: the fixed cost of a tile (first loads, epilogue) outweighs its k-loop.
             // Two half-size workgroups per CU let one's epilogue run under the other's matrix work;
-            // worth it only when the big tile would take more than one round and K is short.
+            // worth it only when the big tile would take more than one round and K is short, and only
+            // where the big tile cannot run in its persistent form, which hides the same cost better.
             const int alt = i == 0 ? kPair256 : i == 1 ? kPair128 : -1;
             const int nkt = a.taps * (a.cin_pad / KT);
             const int ncb = a.n_pad / kTiles[i].bc;
-            if (alt >= 0 && blocks > 256 && nkt <= (i == 1 ? 18 : ncb >= 2 ? 16 : 12))
-                return alt;
+            if (i == 0 && conv_pick_splits(a, 0) == 1 && persist_ok(a, blocks)) return kPersistTile;
+            if (alt >= 0 && blocks > 256 && nkt <= (i == 1 ? 18 : ncb >= 2 ? 16 : 12)) return alt;
             return i;
         }
         const long long work = blocks * kTiles[i].bc * kTiles[i].bp;
@@ -709,7 +956,7 @@ int conv_pick_tile(const ConvArgs& a) {
 // K splits for a layer whose tiles alone cannot fill the chip (only the general epilogue
 // supports it, and only when the caller supplied the scratch).
 int conv_pick_splits(const ConvArgs& a, int tile) {
-    if (a.mode == MODE_RAW) return 1;  // its scratch is written, not accumulated
+    if (a.mode == MODE_RAW || tile == kPersistTile) return 1;  // raw: the scratch is written, not accumulated
     const bool fast = a.mode == MODE_ACT && a.rq_fast && a.n_store % 16 == 0;
     if (fast || !a.partial || tile < 0) return 1;
     const TileCfg& t = kTiles[tile];
@@ -731,16 +978,19 @@ hipError_t launch_conv(const ConvArgs& a_in, hipStream_t stream) {
     if (a.npix <= 0) return hipSuccess;
     const int best = conv_pick_tile(a);
     if (best < 0) return hipErrorInvalidValue;
-    const TileCfg& t = kTiles[best];
+    const bool persist = best == kPersistTile;
+    const TileCfg& t = kTiles[persist ? 0 : best];
     const int npb = (a.npix + t.bp - 1) / t.bp, ncb = a.n_pad / t.bc;
     const int grid = ((npb + 7) / 8) * 8 * ncb;
-    const bool fast = a.mode == MODE_ACT && a.rq_fast && a.n_store % 16 == 0;
-    // EPI_FAST covers signed codes, and unsigned ones only where shortcut and result share the format
-    const bool fast_signed_ok = a.shortcut ? a.sc_unsigned == a.out_unsigned : !a.out_unsigned;
-    const int epi = !fast ? EPI_ANY
-                    : (a.relu && !a.shortcut && a.clamp_hi) ? EPI_FAST_RELU
-                    : fast_signed_ok ? EPI_FAST : EPI_ANY;
+    const int epi = pick_epi(a);
     const int splits = conv_pick_splits(a, best);
+    // Three or more tiles per CU, a fast epilogue and whole rounds of the stage ring: one resident
+    // workgroup per CU walks its tiles and overlaps each tile's first loads with the epilogue before it
+    // (with two tiles per CU the plain kernel was as fast or faster).
+    if (persist) {
+        hipLaunchKernelGGL(kPersist[epi], dim3(g_persist_grid), dim3(t.threads), kPersistLds, stream, a, npb, ncb);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(t.kern[epi], dim3(grid, splits), dim3(t.threads), t.lds, stream, a, npb, ncb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits == 1) return e;
