@@ -22,7 +22,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel, from the two rocprofv3 --pmc runs summarised in
 # profiles/conv_hbm_traffic_cfg4.md (FETCH_SIZE x2.000 + WRITE_SIZE x1.000 against a 1 GiB copy).
 # Only valid for the workload it was measured on.
-PMC_TRAFFIC_BYTES = {("cfg4", 128, "conv_igemm<256,256,2,4,4>"): 202.8e6}
+PMC_TRAFFIC_BYTES = {("cfg4", 128, "conv_igemm_persist<256,256,2,4,4>"): 335.5e6}
 
 
 def main():
