@@ -166,6 +166,11 @@ CONFIGS = {
                          act_unsigned=True),
     "paper_iodf64_u": FlowConfig("paper_iodf64_u", 64, 64, 256, 4, 8, RESNET, 128, 8, True, seed_id=17, block_k2=3,
                                  keep=0.5, keep_levels=(0.75, 0.625, 0.375, 0.25), act_unsigned=True),
+    # residual networks 256 wide over many pixels (800 tiles of 256x256 at level 1): shortcut layers of full
+    # tile width with several tiles per CU, in both activation formats
+    "wide_resnet": FlowConfig("wide_resnet", 64, 64, 200, 2, 2, RESNET, 256, 2, True, seed_id=23, block_k2=3),
+    "wide_resnet_u": FlowConfig("wide_resnet_u", 64, 64, 200, 2, 2, RESNET, 256, 2, True, seed_id=24, block_k2=3,
+                                act_unsigned=True),
     "mini_paper_g": FlowConfig("mini_paper_g", 16, 16, 3, 2, 2, RESNET, 32, 3, True, seed_id=18, block_k2=3,
                                keep=0.5, keep_levels=(0.75, 0.375)),
 }

@@ -95,6 +95,13 @@ def test_paper_network_32_sampled(capsys):
     _sampled(capsys, "paper_res32", CONFIGS["paper_res32"].batch, sample=(0, 300, 511), invariance=(9,), chunk=129)
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["wide_resnet", "wide_resnet_u"])
+def test_wide_residual_network_sampled(capsys, name):
+    # 256-wide shortcut layers on 204800 pixels: the persistent kernel with the shortcut epilogue
+    _sampled(capsys, name, CONFIGS[name].batch, sample=(0, 1, 77, 199), invariance=(5,), chunk=67)
+
+
 @pytest.mark.timeout(900)
 def test_cfg5_batch1(capsys):
     # latency shape: batch 1, the whole image against the oracle
