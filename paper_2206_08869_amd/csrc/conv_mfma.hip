@@ -911,11 +911,11 @@ int pick_epi(const ConvArgs& a) {
     return !fast ? EPI_ANY : (a.relu && !a.shortcut && a.clamp_hi) ? EPI_FAST_RELU : fast_signed_ok ? EPI_FAST : EPI_ANY;
 }
 
-// Whether the 256x256 tile runs in its persistent form: three or more tiles per CU, a fast epilogue
-// and whole rounds of the stage ring (with two tiles per CU the plain kernel was as fast or faster).
+// Whether the 256x256 tile runs in its persistent form: two or more tiles per CU, a fast epilogue
+// and whole rounds of the stage ring.
 bool persist_ok(const ConvArgs& a, long long tiles) {
     const int nkt = a.taps * (a.cin_pad / KT);
-    return pick_epi(a) != EPI_ANY && nkt % 4 == 0 && g_persist_grid >= 8 && tiles >= 3LL * g_persist_grid;
+    return pick_epi(a) != EPI_ANY && nkt % 4 == 0 && g_persist_grid >= 8 && tiles >= 2LL * g_persist_grid;
 }
 
 // First tile in table order that still fills the chip (its two-per-CU half when the reduction is
@@ -984,9 +984,8 @@ hipError_t launch_conv(const ConvArgs& a_in, hipStream_t stream) {
     const int grid = ((npb + 7) / 8) * 8 * ncb;
     const int epi = pick_epi(a);
     const int splits = conv_pick_splits(a, best);
-    // Three or more tiles per CU, a fast epilogue and whole rounds of the stage ring: one resident
-    // workgroup per CU walks its tiles and overlaps each tile's first loads with the epilogue before it
-    // (with two tiles per CU the plain kernel was as fast or faster).
+    // Two or more tiles per CU, a fast epilogue and whole rounds of the stage ring: one resident
+    // workgroup per CU walks its tiles and overlaps each tile's first loads with the epilogue before it.
     if (persist) {
         hipLaunchKernelGGL(kPersist[epi], dim3(g_persist_grid), dim3(t.threads), kPersistLds, stream, a, npb, ncb);
         return hipGetLastError();
