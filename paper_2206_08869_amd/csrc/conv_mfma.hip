@@ -571,10 +571,12 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
 // blockIdx.x, blockIdx.x + gridDim.x, ... The stream of k-tiles runs on across output tiles: once
 // the last k-tile of a tile has been issued the load pointers move to the workgroup's next tile, so
 // the loads that conv_igemm spends on dead stages at the end of its k loop fetch the first k-tiles
-// of the next output tile here, and these land while the epilogue runs. Loads and stores retire in
-// order on one counter: at the start of a tile "at most (NST - 2) * LPT outstanding" still means
-// that its k-tile 0 has landed (the epilogue's stores are younger), and the wait never asks for
-// the stores themselves beyond that. Per-channel constants, the bias included, take the same road
+// of the next output tile here, and these land while the epilogue runs. The epilogue's stores count
+// on the same vmcnt as the tile loads; the waits do not depend on when they complete: tile loads
+// retire in order among themselves, so while a k-tile has not landed, every tile load issued after
+// it is outstanding too, and "at most (NST - 2) * LPT outstanding" cannot hold as long as at least
+// that many tile loads were issued after the k-tile in question - which is the case at every wait,
+// at the start of a tile included. Per-channel constants, the bias included, take the same road
 // as the tiles: four 1 KB loads straight into one of two LDS buffers, issued right behind the last
 // k-tile of the previous output tile, so they too are older than the next tile's k-tile 0.
 template <int BC, int BP, int WC, int WP, int NST, int EPI>
