@@ -39,17 +39,27 @@ class IodfError(RuntimeError):
 
 
 def build_library(verbose=False):
-    """Compile the HIP sources for gfx950 into libiodf.so (in tree)."""
+    """Compile the HIP sources for gfx950 into libiodf.so (in tree): one object per source, in parallel, then link."""
+    from concurrent.futures import ThreadPoolExecutor
     srcs = sorted(glob.glob(os.path.join(_PKG, "csrc", "*.hip")))
-    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-I", os.path.join(_ROOT, "include"), "-o", LIB_PATH] + srcs
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + out)
-    if verbose and out.strip():
-        print(out)
+    objdir = os.path.join(_PKG, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    flags = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-I", os.path.join(_ROOT, "include")]
+
+    def run(cmd):
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + out)
+        return out
+
+    objs = [os.path.join(objdir, os.path.basename(s)[:-4] + ".o") for s in srcs]
+    with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as pool:
+        outs = list(pool.map(lambda so: run(["hipcc"] + flags + ["-c", so[0], "-o", so[1]]), zip(srcs, objs)))
+    outs.append(run(["hipcc", "--offload-arch=gfx950", "-fPIC", "-shared", "-o", LIB_PATH] + objs))
+    if verbose and "".join(outs).strip():
+        print("\n".join(o for o in outs if o.strip()))
     global _LIB
     _LIB = None
     return LIB_PATH

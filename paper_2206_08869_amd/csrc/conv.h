@@ -63,6 +63,7 @@ struct ConvArgs {
     // Unsigned codes (0..255, stored as code - 128): out_unsigned saturates MODE_ACT results to [0, 255]
     // (the layer then has a ReLU); sc_unsigned says the shortcut bytes are such codes.
     int out_unsigned, sc_unsigned;
+    int n_cu;      // compute units of the device the layer runs on (conv_device_cus); decides the launch shape
     int log2_w, log2_hw;  // filled by launch_conv: log2 of w and of h*w when both are powers of two, else -1
     int32_t* partial;  // optional split-K scratch: int32 [npix][n_pad], all zero between launches
     int n_store;   // channels written (<= n_pad); multiple of 4 in MODE_ACT
@@ -94,7 +95,9 @@ int conv_num_tiles();
 const char* conv_tile_name(int tile);
 // Channels x pixels of a tile (0, 0 for an invalid index).
 void conv_tile_dims(int tile, int* bc, int* bp);
-// One-time per-process set-up of kernel attributes (dynamic LDS sizes).
+// Set-up of kernel attributes (dynamic LDS sizes) on the current device.
 hipError_t conv_setup();
+// Compute units of the current device.
+hipError_t conv_device_cus(int* n_cu);
 
 }  // namespace iodf

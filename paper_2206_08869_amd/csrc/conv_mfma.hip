@@ -15,8 +15,6 @@
 // (ky,kx) is the tile of the pixels shifted by (ky-1, kx-1) inside zero-bordered images.
 #include "conv.h"
 
-#include <stdlib.h>
-
 #include <type_traits>
 
 namespace iodf {
@@ -843,16 +841,11 @@ constexpr int kPair256 = 5, kPair128 = 6;  // the two-workgroups-per-CU halves o
 void (*const kPersist[3])(const ConvArgs, int, int) = {nullptr, conv_igemm_persist<256, 256, 2, 4, 4, EPI_FAST>,
                                                         conv_igemm_persist<256, 256, 2, 4, 4, EPI_FAST_RELU>};
 constexpr size_t kPersistLds = (size_t)4 * (256 + 256) * KT + 2 * 4 * 256 * sizeof(int);
-int g_persist_grid = 0;  // workgroups of a persistent launch: one per CU, a multiple of 8 (set by conv_setup)
 constexpr int kPersistTile = kNumTiles;  // what conv_pick_tile answers for a persistent launch of tile 0
 
-int forced_tile() {
-    static int v = [] {
-        const char* e = getenv("IODF_TILE");
-        return e ? atoi(e) : -1;
-    }();
-    return v;
-}
+// Workgroups of a persistent launch: one per compute unit of the device the layer runs on, a
+// multiple of 8 so that a workgroup's tiles stay on its XCD.
+int persist_grid(const ConvArgs& a) { return a.n_cu / 8 * 8; }
 
 bool args_ok(const ConvArgs& a) {
     return !(a.cin_pad <= 0 || a.cin_pad % KT || a.n_pad <= 0 || a.n_pad % 64 || (a.taps != 1 && a.taps != 9) ||
@@ -883,12 +876,14 @@ hipError_t conv_setup() {
                                            (int)kPersistLds);
         if (e != hipSuccess) return e;
     }
-    int dev = 0, cus = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    if (e != hipSuccess) return e;
-    g_persist_grid = cus / 8 * 8;
     return hipSuccess;
+}
+
+hipError_t conv_device_cus(int* n_cu) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+    return e;
 }
 
 int conv_num_tiles() { return kNumTiles + 1; }
@@ -917,7 +912,7 @@ int pick_epi(const ConvArgs& a) {
 // and whole rounds of the stage ring.
 bool persist_ok(const ConvArgs& a, long long tiles) {
     const int nkt = a.taps * (a.cin_pad / KT);
-    return pick_epi(a) != EPI_ANY && nkt % 4 == 0 && g_persist_grid >= 8 && tiles >= 2LL * g_persist_grid;
+    return pick_epi(a) != EPI_ANY && nkt % 4 == 0 && persist_grid(a) >= 8 && tiles >= 2LL * persist_grid(a);
 }
 
 // First tile in table order that still fills the chip (its two-per-CU half when the reduction is
@@ -927,8 +922,6 @@ int conv_pick_tile(const ConvArgs& a) {
     if (!args_ok(a)) return -1;
     int best = -1;
     long long best_blocks = -1, best_work = 0;
-    const int forced = forced_tile();
-    if (forced >= 0 && forced < kNumTiles && a.n_pad % kTiles[forced].bc == 0) return forced;
     for (int i = 0; i < kPair256; ++i) {
         if (a.n_pad % kTiles[i].bc) continue;
         const long long blocks = (long long)((a.npix + kTiles[i].bp - 1) / kTiles[i].bp) *
@@ -989,7 +982,7 @@ hipError_t launch_conv(const ConvArgs& a_in, hipStream_t stream) {
     // Two or more tiles per CU, a fast epilogue and whole rounds of the stage ring: one resident
     // workgroup per CU walks its tiles and overlaps each tile's first loads with the epilogue before it.
     if (persist) {
-        hipLaunchKernelGGL(kPersist[epi], dim3(g_persist_grid), dim3(t.threads), kPersistLds, stream, a, npb, ncb);
+        hipLaunchKernelGGL(kPersist[epi], dim3(persist_grid(a)), dim3(t.threads), kPersistLds, stream, a, npb, ncb);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(t.kern[epi], dim3(grid, splits), dim3(t.threads), t.lds, stream, a, npb, ncb);

@@ -511,6 +511,7 @@ void plan_net(Arena& A, const HostModel& m, const HostNet& N, DevNet& D, int buf
 
 struct iodf_ctx {
     int device = 0, max_batch = 0;
+    int n_cu = 0;     // compute units of `device`
     HostModel shape;  // header fields only are used after init
     std::vector<DevNet> nets;
     std::vector<int> first_net;       // per level (1-based)
@@ -540,8 +541,10 @@ struct iodf_ctx {
     // HIP graph. A graph is captured once per (direction, batch, codes) on an internal stream
     // against internal staging buffers for x, z and codes; a call then is: copy in, graph
     // launch, copy out, all on the caller's stream.
-    struct GraphEntry { int dir, batch, codes; hipGraphExec_t exec; unsigned long long last_use; };
-    std::vector<GraphEntry> graphs;
+    // `done` is recorded after every launch of the graph, so that an entry can be destroyed safely
+    struct GraphEntry { int dir, batch, codes; hipGraphExec_t exec; hipEvent_t done; unsigned long long last_use; };
+    std::vector<GraphEntry> graphs;   // at most kMaxGraphs, least recently used dropped
+    static constexpr size_t kMaxGraphs = 8;
     unsigned long long graph_clock = 0;
     hipStream_t cap_stream = nullptr;
     bool use_graphs = true;
@@ -622,6 +625,7 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
         a.cin_pad = L.cin_pad;
         a.taps = L.taps;
         a.h = h; a.w = w; a.npix = npix;
+        a.n_cu = ctx->n_cu;
         a.wgt = (const int8_t*)(ctx->params + L.wgt_off);
         a.n_pad = L.n_pad;
         a.bias = (const int32_t*)(ctx->params + L.bias_off);
@@ -796,6 +800,7 @@ int iodf_init(iodf_ctx** out, const void* model_blob, size_t blob_bytes, int dev
     // device side
     hipError_t e = hipSetDevice(device_ordinal);
     if (e == hipSuccess) e = conv_setup();
+    if (e == hipSuccess) e = conv_device_cus(&ctx->n_cu);
     if (e != hipSuccess) { g_last_hip = (int)e; delete ctx; return IODF_E_HIP; }
     auto dev_alloc = [&](void** p, size_t bytes) -> bool {
         if (bytes == 0) bytes = 256;
@@ -882,7 +887,11 @@ void iodf_free(iodf_ctx* ctx) {
     for (void* q : {(void*)ctx->codec_sig, (void*)ctx->codec_inv, (void*)ctx->codec_z, (void*)ctx->codec_codes,
                     (void*)ctx->lane_words, (void*)ctx->lane_meta, (void*)ctx->codec_errs})
         if (q) (void)hipFree(q);
-    for (auto& g : ctx->graphs) (void)hipGraphExecDestroy(g.exec);
+    for (auto& g : ctx->graphs) {
+        (void)hipEventSynchronize(g.done);
+        (void)hipGraphExecDestroy(g.exec);
+        (void)hipEventDestroy(g.done);
+    }
     if (ctx->cap_stream) (void)hipStreamDestroy(ctx->cap_stream);
     if (ctx->stage_x) (void)hipFree(ctx->stage_x);
     if (ctx->stage_z) (void)hipFree(ctx->stage_z);
@@ -940,12 +949,12 @@ static int enqueue_inverse(iodf_ctx* ctx, const int32_t* z_dev, int batch, uint8
 }
 
 // Find or capture the graph of one call shape. Returns nullptr (and *rc) when capture fails.
-static hipGraphExec_t get_graph(iodf_ctx* ctx, int dir, int batch, int codes, int* rc) {
+static iodf_ctx::GraphEntry* get_graph(iodf_ctx* ctx, int dir, int batch, int codes, int* rc) {
     *rc = IODF_OK;
     for (auto& g : ctx->graphs)
         if (g.dir == dir && g.batch == batch && g.codes == codes) {
             g.last_use = ++ctx->graph_clock;
-            return g.exec;
+            return &g;
         }
     hipError_t e = hipStreamBeginCapture(ctx->cap_stream, hipStreamCaptureModeThreadLocal);
     if (e != hipSuccess) { g_last_hip = (int)e; *rc = IODF_E_HIP; return nullptr; }
@@ -964,15 +973,22 @@ static hipGraphExec_t get_graph(iodf_ctx* ctx, int dir, int batch, int codes, in
     e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
     (void)hipGraphDestroy(graph);
     if (e != hipSuccess) { g_last_hip = (int)e; *rc = IODF_E_HIP; return nullptr; }
-    if (ctx->graphs.size() >= 8) {  // drop the least recently used shape
+    hipEvent_t done = nullptr;
+    e = hipEventCreateWithFlags(&done, hipEventDisableTiming);
+    if (e != hipSuccess) { (void)hipGraphExecDestroy(exec); g_last_hip = (int)e; *rc = IODF_E_HIP; return nullptr; }
+    if (ctx->graphs.size() >= iodf_ctx::kMaxGraphs) {
+        // Drop the least recently used shape. Calls never synchronise, so its last replay may still be
+        // running on the caller's stream: wait for the event recorded behind that replay first.
         size_t victim = 0;
         for (size_t i = 1; i < ctx->graphs.size(); ++i)
             if (ctx->graphs[i].last_use < ctx->graphs[victim].last_use) victim = i;
+        (void)hipEventSynchronize(ctx->graphs[victim].done);
         (void)hipGraphExecDestroy(ctx->graphs[victim].exec);
+        (void)hipEventDestroy(ctx->graphs[victim].done);
         ctx->graphs.erase(ctx->graphs.begin() + (long)victim);
     }
-    ctx->graphs.push_back({dir, batch, codes, exec, ++ctx->graph_clock});
-    return exec;
+    ctx->graphs.push_back({dir, batch, codes, exec, done, ++ctx->graph_clock});
+    return &ctx->graphs.back();
 }
 
 int iodf_forward(iodf_ctx* ctx, const uint8_t* x_dev, int batch, int32_t* z_dev, int8_t* codes_dev, void* stream) {
@@ -985,10 +1001,11 @@ int iodf_forward(iodf_ctx* ctx, const uint8_t* x_dev, int batch, int32_t* z_dev,
     if (!ctx->use_graphs || ctx->prof_on) return enqueue_forward(ctx, x_dev, batch, z_dev, codes_dev, st);
     const int codes = (codes_dev && ctx->d_codes) ? 1 : 0;
     int rc;
-    hipGraphExec_t exec = get_graph(ctx, 0, batch, codes, &rc);
-    if (!exec) return rc;
+    iodf_ctx::GraphEntry* g = get_graph(ctx, 0, batch, codes, &rc);
+    if (!g) return rc;
     HIP_TRY(hipMemcpyAsync(ctx->stage_x, x_dev, (size_t)batch * ctx->d, hipMemcpyDeviceToDevice, st));
-    HIP_TRY(hipGraphLaunch(exec, st));
+    HIP_TRY(hipGraphLaunch(g->exec, st));
+    HIP_TRY(hipEventRecord(g->done, st));
     HIP_TRY(hipMemcpyAsync(z_dev, ctx->stage_z, 4 * (size_t)batch * ctx->d, hipMemcpyDeviceToDevice, st));
     if (codes)
         HIP_TRY(hipMemcpyAsync(codes_dev, ctx->stage_codes, (size_t)batch * ctx->d_codes, hipMemcpyDeviceToDevice, st));
@@ -1004,10 +1021,11 @@ int iodf_inverse(iodf_ctx* ctx, const int32_t* z_dev, int batch, uint8_t* x_dev,
     HIP_TRY(hipSetDevice(ctx->device));
     if (!ctx->use_graphs || ctx->prof_on) return enqueue_inverse(ctx, z_dev, batch, x_dev, st);
     int rc;
-    hipGraphExec_t exec = get_graph(ctx, 1, batch, 0, &rc);
-    if (!exec) return rc;
+    iodf_ctx::GraphEntry* g = get_graph(ctx, 1, batch, 0, &rc);
+    if (!g) return rc;
     HIP_TRY(hipMemcpyAsync(ctx->stage_z, z_dev, 4 * (size_t)batch * ctx->d, hipMemcpyDeviceToDevice, st));
-    HIP_TRY(hipGraphLaunch(exec, st));
+    HIP_TRY(hipGraphLaunch(g->exec, st));
+    HIP_TRY(hipEventRecord(g->done, st));
     HIP_TRY(hipMemcpyAsync(x_dev, ctx->stage_x, (size_t)batch * ctx->d, hipMemcpyDeviceToDevice, st));
     return IODF_OK;
 }
@@ -1196,6 +1214,8 @@ int iodf_conv_probe(int device_ordinal, int c_in, int c_out, int k, int h, int w
         if (shift_host[c] > 62 || m_host[c] < 0 || bias_host[c] >= (1 << 30) || bias_host[c] <= -(1 << 30)) return IODF_E_ARG;
     HIP_TRY(hipSetDevice(device_ordinal));
     HIP_TRY(conv_setup());
+    int n_cu = 0;
+    HIP_TRY(conv_device_cus(&n_cu));
     std::vector<uint8_t> gate((size_t)c_out, 1);
     HostLayer L{c_out, c_in, k, relu ? 1 : 0, 0, w_host, bias_host, m_host, shift_host, gate.data()};
     Arena A;
@@ -1242,6 +1262,7 @@ int iodf_conv_probe(int device_ordinal, int c_in, int c_out, int k, int h, int w
     ConvArgs a;
     memset(&a, 0, sizeof(a));
     a.in = din; a.in_plane = plane; a.cin_pad = cin_pad; a.taps = k * k; a.h = h; a.w = w; a.npix = batch * h * w;
+    a.n_cu = n_cu;
     a.wgt = (const int8_t*)(params + D.wgt_off); a.n_pad = n_pad;
     a.bias = (const int32_t*)(params + D.bias_off); a.mul = (const int32_t*)(params + D.mul_off);
     a.shift = (const int32_t*)(params + D.shift_off); a.rq_fast = D.rq_fast;
