@@ -44,7 +44,8 @@ enum {
     IODF_E_SHAPE = -3,  /* blob is well formed but its layers do not fit the declared family */
     IODF_E_BATCH = -4,  /* batch < 0 or batch > max_batch */
     IODF_E_HIP = -5,    /* a HIP runtime call failed (iodf_last_hip_error has the code) */
-    IODF_E_NOMEM = -6   /* host or device allocation failed */
+    IODF_E_NOMEM = -6,  /* host or device allocation failed */
+    IODF_E_SCRATCH = -7 /* iodf_encode_noalloc: the batch needs more than the static scratch holds */
 };
 
 /* What iodf_query reports. */
@@ -66,8 +67,9 @@ enum {
     IODF_Q_CODEC_CLAMPED = 13,      /* latents whose residual z - mu left [-8192, 8191] and was clamped (the image
                                        then does NOT decode back); 13..15 synchronise and reset like RANGE_ERRORS */
     IODF_Q_CODEC_OVERFLOWS = 14,    /* containers that needed more than cap_words (truncated, unusable) */
-    IODF_Q_CODEC_BROKEN_LANES = 15  /* coder lanes that iodf_decode could not read back to their initial state
+    IODF_Q_CODEC_BROKEN_LANES = 15, /* coder lanes that iodf_decode could not read back to their initial state
                                        (malformed or foreign container) */
+    IODF_Q_NOALLOC_MAX_BATCH = 16   /* largest batch iodf_encode_noalloc accepts for this model (<= max_batch) */
 };
 
 /*
@@ -151,6 +153,23 @@ int iodf_encode(iodf_ctx* ctx, const uint8_t* x_dev, int batch, uint32_t* words_
                 uint32_t* sizes_dev, void* stream);
 int iodf_decode(iodf_ctx* ctx, const uint32_t* words_dev, int64_t cap_words, int batch, uint8_t* x_dev, void* stream);
 int iodf_codec_tables(int32_t* sig_host, int64_t* inv_host);
+
+/*
+ * iodf_encode for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc. Same arguments, same containers, word for word.
+ * The coder's working buffers (the batch's latents and codes, the words each lane sheds, lane
+ * states, the prior's tables and the error counters), which iodf_encode allocates on its first
+ * call, live in a 64 MiB array that is part of the library's device image; each GPU holds one copy
+ * from the moment the library is loaded until the process ends, and iodf_init prepares it. The call
+ * allocates and frees nothing and launches the flow kernel by kernel instead of replaying a graph.
+ * A batch whose buffers do not fit returns IODF_E_SCRATCH before anything is enqueued
+ * (IODF_Q_NOALLOC_MAX_BATCH tells the limit for a model: 554 images of 3x64x64 with prior heads on four levels).
+ * All contexts on one GPU share that GPU's array: calls that overlap on one GPU (from any context,
+ * on any streams) race; serialise them. The error counters of these calls are shared per GPU too and
+ * are reported, and reset, by iodf_query(IODF_Q_CODEC_*) of any context that used this entry point.
+ */
+int iodf_encode_noalloc(iodf_ctx* ctx, const uint8_t* x_dev, int batch, uint32_t* words_dev, int64_t cap_words,
+                        uint32_t* sizes_dev, void* stream);
 
 /*
  * Patch-based coding of images larger than the flow's H x W (Sec. 5.2: a large image is coded as

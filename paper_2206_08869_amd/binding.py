@@ -19,12 +19,12 @@ _LIB = None
 IODF_Q_Z_ELEMS, IODF_Q_CODE_BYTES, IODF_Q_WORKSPACE_BYTES, IODF_Q_MACS_FORWARD, IODF_Q_MACS_INVERSE, \
     IODF_Q_RANGE_ERRORS, IODF_Q_MAX_BATCH, IODF_Q_IMAGE_H, IODF_Q_IMAGE_W, IODF_Q_CONV_LAUNCHES, \
     IODF_Q_WIDE_MACS_FORWARD, IODF_Q_CODEC_HEADER_WORDS, IODF_Q_CODEC_MAX_WORDS, IODF_Q_CODEC_CLAMPED, \
-    IODF_Q_CODEC_OVERFLOWS, IODF_Q_CODEC_BROKEN_LANES = range(16)
+    IODF_Q_CODEC_OVERFLOWS, IODF_Q_CODEC_BROKEN_LANES, IODF_Q_NOALLOC_MAX_BATCH = range(17)
 
 EXPORTS = ["iodf_init", "iodf_forward", "iodf_inverse", "iodf_query", "iodf_free", "iodf_strerror",
            "iodf_last_hip_error", "iodf_profile_begin", "iodf_profile_end", "iodf_prior_cf", "iodf_encode",
            "iodf_decode", "iodf_codec_tables", "iodf_tile_patches", "iodf_untile_patches",
-           "iodf_conv_probe"]
+           "iodf_conv_probe", "iodf_encode_noalloc"]
 
 
 class KernelStat(ctypes.Structure):
@@ -96,6 +96,8 @@ def load_library(build_if_missing=True):
     L.iodf_prior_cf.argtypes = [vp, vp, vp, ci, vp, vp, vp]
     L.iodf_encode.restype = ci
     L.iodf_encode.argtypes = [vp, vp, ci, vp, ctypes.c_int64, vp, vp]
+    L.iodf_encode_noalloc.restype = ci
+    L.iodf_encode_noalloc.argtypes = [vp, vp, ci, vp, ctypes.c_int64, vp, vp]
     L.iodf_decode.restype = ci
     L.iodf_decode.argtypes = [vp, vp, ctypes.c_int64, ci, vp, vp]
     L.iodf_codec_tables.restype = ci
@@ -144,6 +146,10 @@ def iodf_prior_cf(ctx, z_ptr, codes_ptr, batch, c_ptr, f_ptr, stream):
 
 def iodf_encode(ctx, x_ptr, batch, words_ptr, cap_words, sizes_ptr, stream):
     _check(load_library().iodf_encode(ctx, x_ptr, int(batch), words_ptr, int(cap_words), sizes_ptr, stream))
+
+
+def iodf_encode_noalloc(ctx, x_ptr, batch, words_ptr, cap_words, sizes_ptr, stream):
+    _check(load_library().iodf_encode_noalloc(ctx, x_ptr, int(batch), words_ptr, int(cap_words), sizes_ptr, stream))
 
 
 def iodf_decode(ctx, words_ptr, cap_words, batch, x_ptr, stream):
@@ -268,8 +274,9 @@ class Flow:
                       self._stream())
         return C, F
 
-    def encode(self, x, cap_words=None, words=None, sizes=None):
-        """x u8 [B,3,H,W] -> (containers int32-viewed-as-u32 [B,cap_words], sizes [B] in words)."""
+    def encode(self, x, cap_words=None, words=None, sizes=None, noalloc=False):
+        """x u8 [B,3,H,W] -> (containers int32-viewed-as-u32 [B,cap_words], sizes [B] in words).
+        noalloc=True calls iodf_encode_noalloc (pass `words` and `sizes`: the call itself allocates nothing)."""
         torch = self._torch
         assert x.is_cuda and x.dtype == torch.uint8 and x.is_contiguous()
         b = x.shape[0]
@@ -278,7 +285,7 @@ class Flow:
             words = torch.zeros((b, cap), dtype=torch.int32, device=self.device)
         if sizes is None:
             sizes = torch.zeros((b,), dtype=torch.int32, device=self.device)
-        iodf_encode(self._ctx, ctypes.c_void_p(x.data_ptr()) if b else None, b,
+        (iodf_encode_noalloc if noalloc else iodf_encode)(self._ctx, ctypes.c_void_p(x.data_ptr()) if b else None, b,
                     ctypes.c_void_p(words.data_ptr()) if b else None, cap,
                     ctypes.c_void_p(sizes.data_ptr()) if b else None, self._stream())
         return words, sizes

@@ -10,6 +10,7 @@
 #include <climits>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -553,6 +554,7 @@ struct iodf_ctx {
     int8_t* stage_codes = nullptr;
     // Compressor (iodf_encode / iodf_decode / iodf_prior_cf): allocated by the first call that needs it
     bool codec_ready = false;
+    bool used_static_scratch = false;  // iodf_encode_noalloc ran: its error counters live in the static scratch
     ChunkTable chunks;                 // chunk c = level c + 1
     long long lane_words_per_image = 0;
     int32_t* codec_sig = nullptr;      // tables of the integer prior
@@ -696,6 +698,9 @@ static const int32_t* partial_of(const iodf_ctx* ctx) { return ctx->raw; }
 
 extern "C" {
 
+static int codec_layout(iodf_ctx* ctx);
+static int scratch_setup(int device);
+
 int iodf_last_hip_error(void) { return g_last_hip; }
 
 const char* iodf_strerror(int code) {
@@ -707,6 +712,7 @@ const char* iodf_strerror(int code) {
         case IODF_E_BATCH: return "batch outside [0, max_batch]";
         case IODF_E_HIP: return "HIP runtime error";
         case IODF_E_NOMEM: return "out of memory";
+        case IODF_E_SCRATCH: return "batch needs more than the 64 MiB static scratch of iodf_encode_noalloc";
         default: return "unknown error";
     }
 }
@@ -755,6 +761,7 @@ int iodf_init(iodf_ctx** out, const void* model_blob, size_t blob_bytes, int dev
         }
         ctx->d_codes = co;
     }
+    (void)codec_layout(ctx);  // cannot fail: parse_blob bounds the number of levels
 
     // plan: pack weights (gate compaction), constants and composed permutations
     Arena A;
@@ -802,6 +809,8 @@ int iodf_init(iodf_ctx** out, const void* model_blob, size_t blob_bytes, int dev
     if (e == hipSuccess) e = conv_setup();
     if (e == hipSuccess) e = conv_device_cus(&ctx->n_cu);
     if (e != hipSuccess) { g_last_hip = (int)e; delete ctx; return IODF_E_HIP; }
+    rc = scratch_setup(device_ordinal);
+    if (rc != IODF_OK) { delete ctx; return rc; }
     auto dev_alloc = [&](void** p, size_t bytes) -> bool {
         if (bytes == 0) bytes = 256;
         hipError_t er = hipMalloc(p, bytes);
@@ -1032,9 +1041,8 @@ int iodf_inverse(iodf_ctx* ctx, const int32_t* z_dev, int batch, uint8_t* x_dev,
 
 // ---- compressor: flow + prior + coder ----
 
-// Device buffers and tables of the compressor, on first use.
-static int codec_prepare(iodf_ctx* ctx) {
-    if (ctx->codec_ready) return IODF_OK;
+// Where the chunks of one image's latents, codes and coder lanes live (host arithmetic only).
+static int codec_layout(iodf_ctx* ctx) {
     const HostModel& m = ctx->shape;
     if (m.levels > kMaxChunks) return IODF_E_ARG;
     ChunkTable& ct = ctx->chunks;
@@ -1053,6 +1061,14 @@ static int codec_prepare(iodf_ctx* ctx) {
         lane_off += (long long)kLanes * ct.lane_cap[lv - 1];
     }
     ctx->lane_words_per_image = lane_off;
+    return IODF_OK;
+}
+
+// Device buffers and tables of the compressor, on first use.
+static int codec_prepare(iodf_ctx* ctx) {
+    if (ctx->codec_ready) return IODF_OK;
+    const ChunkTable& ct = ctx->chunks;
+    const long long lane_off = ctx->lane_words_per_image;
     std::vector<int32_t> sig(kSigEntries);
     std::vector<int64_t> inv(256);
     codec_make_tables(sig.data(), inv.data());
@@ -1124,6 +1140,91 @@ int iodf_encode(iodf_ctx* ctx, const uint8_t* x_dev, int batch, uint32_t* words_
     PROF_LAUNCH(ctx, st, CLS_RANS_PACK, 0, 0,
                 launch_rans_pack(ctx->chunks, ctx->lane_words, ctx->lane_words_per_image, ctx->lane_meta, batch,
                                  words_dev, cap_words, sizes_dev, ctx->codec_errs, st));
+    return IODF_OK;
+}
+
+// ---- iodf_encode for callers that cannot allocate ----
+//
+// iodf_encode keeps the coder's device buffers (latents and codes of the batch, the words each lane
+// sheds, lane states, the two prior tables, three error counters) in memory that its first call
+// allocates. iodf_encode_noalloc keeps the same buffers in this file-scope array instead. Each GPU
+// the library runs on holds its own copy of the array at its own address until the process ends;
+// host code never uses the array's name as an address, only what hipGetSymbolAddress returned for
+// the device at hand.
+constexpr size_t kScratchBytes = (size_t)64 << 20;
+constexpr size_t kScratchErrsOff = 0;                         // u64[3], kept across calls
+constexpr size_t kScratchSigOff = 256;                        // i32[kSigEntries]
+constexpr size_t kScratchInvOff = kScratchSigOff + ((sizeof(int32_t) * kSigEntries + 255) & ~(size_t)255);
+constexpr size_t kScratchCallOff = kScratchInvOff + sizeof(int64_t) * 256;   // per-call buffers from here
+static_assert(kScratchCallOff % 256 == 0, "per-call region must stay aligned");
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static unsigned char* g_scratch_ptr[kMaxDevices];   // device address of `scratch` per device, nullptr = not set up
+static std::mutex g_scratch_mutex;
+
+static size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+// Once per device, with that device current (iodf_init calls this): resolve the array's address on
+// the device, upload the prior tables, clear the counters.
+static int scratch_setup(int device) {
+    if (device < 0 || device >= kMaxDevices) return IODF_E_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device]) return IODF_OK;
+    unsigned char* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) { g_last_hip = (int)hipErrorInvalidSymbol; return IODF_E_HIP; }
+    std::vector<int32_t> sig(kSigEntries);
+    std::vector<int64_t> inv(256);
+    codec_make_tables(sig.data(), inv.data());
+    HIP_TRY(hipMemcpy(ptr + kScratchSigOff, sig.data(), sizeof(int32_t) * kSigEntries, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(ptr + kScratchInvOff, inv.data(), sizeof(int64_t) * 256, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemset(ptr + kScratchErrsOff, 0, 3 * sizeof(unsigned long long)));
+    HIP_TRY(hipDeviceSynchronize());
+    g_scratch_ptr[device] = ptr;
+    return IODF_OK;
+}
+
+// Bytes of the per-call region a batch needs: latents, codes, lane words, lane states.
+static size_t scratch_need(const iodf_ctx* ctx, long long batch) {
+    const size_t B = (size_t)batch;
+    return align256(4 * B * (size_t)ctx->d) + align256(B * (size_t)std::max<long long>(ctx->d_codes, 1)) +
+           align256(4 * B * (size_t)ctx->lane_words_per_image) + align256(16 * B * (size_t)ctx->chunks.n_chunks * kLanes);
+}
+
+int iodf_encode_noalloc(iodf_ctx* ctx, const uint8_t* x_dev, int batch, uint32_t* words_dev, int64_t cap_words,
+                        uint32_t* sizes_dev, void* stream) {
+    if (!ctx) return IODF_E_ARG;
+    if (batch < 0 || batch > ctx->max_batch) return IODF_E_BATCH;
+    if (batch == 0) return IODF_OK;
+    if (!x_dev || !words_dev || !sizes_dev || cap_words < 1) return IODF_E_ARG;
+    if (scratch_need(ctx, batch) > kScratchBytes - kScratchCallOff) return IODF_E_SCRATCH;
+    unsigned char* const ptr = g_scratch_ptr[ctx->device];  // set by iodf_init on this device
+    if (!ptr) return IODF_E_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipSetDevice(ctx->device));
+    // carve the per-call region; every word read below is written by this call first (the flow writes
+    // all latents and codes of the batch, the coder writes each lane's state and the words it counts),
+    // so nothing has to be cleared and what an earlier, larger call left behind is never read
+    const size_t B = (size_t)batch;
+    unsigned char* q = ptr + kScratchCallOff;
+    int32_t* zbuf = (int32_t*)q;            q += align256(4 * B * (size_t)ctx->d);
+    int8_t* cbuf = (int8_t*)q;              q += align256(B * (size_t)std::max<long long>(ctx->d_codes, 1));
+    uint32_t* lane_words = (uint32_t*)q;    q += align256(4 * B * (size_t)ctx->lane_words_per_image);
+    uint32_t* lane_meta = (uint32_t*)q;
+    unsigned long long* errs = (unsigned long long*)(ptr + kScratchErrsOff);
+    const CodecTables t{(const int32_t*)(ptr + kScratchSigOff), (const int64_t*)(ptr + kScratchInvOff)};
+    // the flow, launched kernel by kernel (a HIP graph would be instantiated, which allocates)
+    int rc = enqueue_forward(ctx, x_dev, batch, zbuf, ctx->d_codes ? cbuf : nullptr, st);
+    if (rc != IODF_OK) return rc;
+    ctx->used_static_scratch = true;
+    const int8_t* codes = ctx->d_codes ? cbuf : nullptr;
+    PROF_LAUNCH(ctx, st, CLS_RANS_ENCODE, 0, (long long)batch * (4 * ctx->d + ctx->d_codes),
+                launch_rans_encode(t, ctx->chunks, zbuf, ctx->d, codes, ctx->d_codes, batch, lane_words,
+                                   ctx->lane_words_per_image, lane_meta, errs, st));
+    PROF_LAUNCH(ctx, st, CLS_RANS_PACK, 0, 0,
+                launch_rans_pack(ctx->chunks, lane_words, ctx->lane_words_per_image, lane_meta, batch, words_dev,
+                                 cap_words, sizes_dev, errs, st));
     return IODF_OK;
 }
 
@@ -1389,14 +1490,31 @@ int iodf_query(iodf_ctx* ctx, int what, int64_t* out) {
         case IODF_Q_CODEC_CLAMPED:
         case IODF_Q_CODEC_OVERFLOWS:
         case IODF_Q_CODEC_BROKEN_LANES: {
-            if (!ctx->codec_ready) { *out = 0; return IODF_OK; }
+            *out = 0;
+            if (!ctx->codec_ready && !ctx->used_static_scratch) return IODF_OK;
             HIP_TRY(hipSetDevice(ctx->device));
             HIP_TRY(hipDeviceSynchronize());
-            unsigned long long* p = ctx->codec_errs + (what - IODF_Q_CODEC_CLAMPED);
-            unsigned long long v = 0;
-            HIP_TRY(hipMemcpy(&v, p, sizeof(v), hipMemcpyDeviceToHost));
-            HIP_TRY(hipMemset(p, 0, sizeof(v)));
-            *out = (int64_t)v;
+            unsigned long long* where[2] = {
+                ctx->codec_ready ? ctx->codec_errs + (what - IODF_Q_CODEC_CLAMPED) : nullptr,
+                ctx->used_static_scratch
+                    ? (unsigned long long*)(g_scratch_ptr[ctx->device] + kScratchErrsOff) + (what - IODF_Q_CODEC_CLAMPED)
+                    : nullptr};
+            for (unsigned long long* p : where) {
+                if (!p) continue;
+                unsigned long long v = 0;
+                HIP_TRY(hipMemcpy(&v, p, sizeof(v), hipMemcpyDeviceToHost));
+                HIP_TRY(hipMemset(p, 0, sizeof(v)));
+                *out += (int64_t)v;
+            }
+            return IODF_OK;
+        }
+        case IODF_Q_NOALLOC_MAX_BATCH: {
+            long long lo = 0, hi = ctx->max_batch;  // the need grows with the batch: bisect
+            while (lo < hi) {
+                const long long mid = (lo + hi + 1) / 2;
+                if (scratch_need(ctx, mid) <= kScratchBytes - kScratchCallOff) lo = mid; else hi = mid - 1;
+            }
+            *out = lo;
             return IODF_OK;
         }
         default: return IODF_E_ARG;
