@@ -55,12 +55,15 @@ __device__ __forceinline__ int rq_in(int a, int M, int s) {
     return r > 127 ? 127 : (r < -128 ? -128 : (int)r);
 }
 
-// Codes of channel c < n_a of pixel p: sat8(rq(S[p][idx[c]]; M, s)); channels n_a..cpad-1 are 0.
+// Codes of channel c < n_a of pixel p: sat8(rq(S[p][idx[c]]; M, s)).
 // xq is laid out in 64-channel planes of zero-bordered images (see conv.h): channel c of pixel
-// (b, i, j) at xq[(c / 64) * plane + pos(b, i, j) * 64 + c % 64]. One thread per 4 channels.
+// (b, i, j) at xq[(c / 64) * plane + pos(b, i, j) * 64 + c % 64]. One thread per 4 channels; only the
+// dwords that hold a real channel are written: the padding channels up to the next multiple of 64 were
+// zeroed when the buffer was allocated and nothing ever writes them (every network of a level reads the
+// same number of channels), which at the first level saves seven eighths of the pass's stores.
 __global__ void k_quant_in(const int32_t* __restrict__ S, int npix, int h, int w, int C, const int32_t* __restrict__ idx,
-                           int n_a, int M, int s, int8_t* __restrict__ xq, int cpad, long long plane) {
-    const int groups = cpad / 4;
+                           int n_a, int M, int s, int8_t* __restrict__ xq, long long plane) {
+    const int groups = (n_a + 3) / 4;
     const long long n = (long long)npix * groups;
     const int hw = h * w, W2 = w + 2, PP = (h + 2) * W2;
     for (long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x; t < n; t += (long long)gridDim.x * blockDim.x) {
@@ -186,8 +189,8 @@ hipError_t launch_quant_in(const int32_t* S, int npix, int h, int w, int C, cons
     if (cpad % 64 || n_a > cpad || h < 1 || w < 1 || npix % (h * w) ||
         plane < (long long)(npix / (h * w)) * (h + 2) * (w + 2) * 64)
         return hipErrorInvalidValue;
-    hipLaunchKernelGGL(k_quant_in, dim3(grid_for((long long)npix * (cpad / 4))), dim3(TPB), 0, st, S, npix, h, w, C, idx,
-                       n_a, M, s, xq, cpad, plane);
+    hipLaunchKernelGGL(k_quant_in, dim3(grid_for((long long)npix * ((n_a + 3) / 4))), dim3(TPB), 0, st, S, npix, h, w, C,
+                       idx, n_a, M, s, xq, plane);
     return hipGetLastError();
 }
 

@@ -67,14 +67,24 @@ def _sampled(capsys, name, batch, sample, invariance=(), chunk=None):
         assert np.array_equal(cc[i], c_ref[0]), "codes differ from oracle at image %d" % i
 
 
+def _spread(batch, n, seed):
+    """n image indices of a batch: the first four and the last two (the first and the last tiles of every
+    level, whose pixel tiles hold one to sixteen images), two pairs of neighbours around the middle (images
+    that share a tile at the deep levels), and seeded others."""
+    fixed = [0, 1, 2, 3, batch // 2 - 1, batch // 2, batch // 2 + 3, batch // 2 + 4, batch - 2, batch - 1]
+    rng = np.random.default_rng(seed)
+    rest = [int(i) for i in rng.permutation(batch) if int(i) not in fixed]
+    return tuple(sorted(fixed + rest[:max(0, n - len(fixed))]))
+
+
 @pytest.mark.timeout(600)
 def test_cfg3_sampled(capsys):
-    _sampled(capsys, "cfg3", CONFIGS["cfg3"].batch, sample=(0, 64, 131, 200, 255), invariance=(7,), chunk=53)
+    _sampled(capsys, "cfg3", CONFIGS["cfg3"].batch, sample=_spread(256, 32, 3), invariance=(7,), chunk=53)
 
 
 @pytest.mark.timeout(900)
 def test_cfg4_sampled(capsys):
-    _sampled(capsys, "cfg4", CONFIGS["cfg4"].batch, sample=(0, 77, 127), invariance=(64,), chunk=37)
+    _sampled(capsys, "cfg4", CONFIGS["cfg4"].batch, sample=_spread(128, 24, 4), invariance=(64,), chunk=37)
 
 
 @pytest.mark.timeout(600)
@@ -111,7 +121,7 @@ def test_cfg5_batch1(capsys):
 @pytest.mark.timeout(900)
 def test_cfg5_batch1024_sampled(capsys):
     # throughput shape; oracle on sampled images, batch invariance on the others
-    _sampled(capsys, "cfg5", 1024, sample=(0, 300, 777, 1023), invariance=(1, 511), chunk=301)
+    _sampled(capsys, "cfg5", 1024, sample=_spread(1024, 16, 5), invariance=(1, 511), chunk=301)
 
 
 def _codec_full(capsys, name, batch, sample):

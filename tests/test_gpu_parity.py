@@ -260,3 +260,57 @@ def _check_single_convolution(c_in, c_out, k, relu, shift_lo, b, h, w):
         ref = oracle.epilogue(oracle.conv_acc(x[i], W, bias), M, shift, relu=relu)
         assert np.array_equal(y[i], ref), "image %d" % i
     assert us > 0
+
+
+def _edge_accumulators(M, shift, top):
+    """Per channel, the smallest accumulator a >= 0 whose requantised value round_half_away(a * M / 2^shift)
+    reaches `top`: a * M >= (top - 1/2) * 2^shift (exact integer arithmetic)."""
+    out = []
+    for m, s in zip(M.tolist(), shift.tolist()):
+        need = (2 * top - 1) << (s - 1)
+        out.append(-(-need // m))
+    return np.array(out, dtype=np.int64)
+
+
+@pytest.mark.parametrize("relu,edge", [(True, "top"), (True, "zero"), (False, "top"), (False, "bottom"), (False, "zero")])
+@pytest.mark.parametrize("b,side,c_in", [(2, 16, 64), (136, 32, 256)])
+def test_epilogue_at_the_saturation_edges(relu, edge, b, side, c_in):
+    """Accumulators placed, for every output channel, exactly around the points where the epilogue's
+    result changes regime: the smallest accumulator that requantises to 127 (the fast ReLU epilogue clamps
+    the accumulator there BEFORE it rescales), its counterpart at -128 for layers without ReLU, and zero.
+    A 1x1 layer whose only non-zero weights are +1 and -1 on two input channels adds delta in -3..3 to a
+    per-channel bias, so pixel p of channel c sees bias[c] + delta(p). Small case: the plain kernel; large
+    case (139264 pixels, 4 k-tiles): the persistent kernel."""
+    import oracle
+    c_out = 256
+    rng = np.random.default_rng(77 + b)
+    M = rng.integers(1 << 30, (1 << 31) - 1, c_out).astype(np.int32)
+    shift = rng.integers(33, 47, c_out).astype(np.uint8)
+    if edge == "top":
+        bias = _edge_accumulators(M, shift, 127)
+    elif edge == "bottom":
+        bias = -_edge_accumulators(M, shift, 128)
+    else:
+        bias = np.zeros(c_out, np.int64)
+    assert np.abs(bias).max() < (1 << 30)
+    bias = bias.astype(np.int32)
+    W = np.zeros((c_out, c_in, 1, 1), np.int8)
+    W[:, 0] = 1
+    W[:, 1] = -1
+    x = rng.integers(0, 128, (b, c_in, side, side)).astype(np.int8)   # other channels: arbitrary, zero weights
+    delta = (np.arange(b * side * side) % 7 - 3).reshape(b, side, side)
+    x[:, 0] = np.maximum(delta, 0)
+    x[:, 1] = np.maximum(-delta, 0)
+    y, _ = iodf.iodf_conv_probe(x, W, bias, M, shift, relu=relu, iters=1)
+    seen = set()
+    for i in range(b):
+        ref = oracle.epilogue(oracle.conv_acc(x[i], W, bias), M, shift, relu=relu)
+        assert np.array_equal(y[i], ref), "image %d" % i
+        seen.update(np.unique(ref).tolist())
+    # the cases straddle the edge they aim at
+    if edge == "top":
+        assert 127 in seen and 126 in seen
+    elif edge == "bottom":
+        assert -128 in seen and -127 in seen
+    else:
+        assert 0 in seen
