@@ -259,6 +259,58 @@ def other_runs(iodf, main_flow, main_cfg, x, z, codes, x_out, args):
     return out
 
 
+def layer_clock(iodf, np):
+    """Isolated wide layers of cfg4 (batch 128), each launched back to back for about half a second: time
+    per launch, the engine clock the driver reports meanwhile, and what the kernel's own per-tile
+    timeline says (clock of the compute units from the shader-clock and the 100 MHz counters, time a
+    workgroup waits for a tile's first operands, k loop, epilogue)."""
+    from synth import prng
+    from synth.model import normalise_scale
+    iodf.load_library()
+    rows = []
+    #        c_in  k  side  expected us (sizes the run)
+    shapes = [(512, 3, 32, 280), (2048, 1, 32, 140), (512, 1, 32, 50), (512, 3, 16, 60), (512, 3, 8, 25), (512, 3, 4, 19)]
+    for c_in, k, side, est_us in shapes:
+        b, c_out = 128, 512
+        n = b * c_in * side * side
+        # Data with the statistics of a hidden layer of the synthetic flows: post-ReLU codes (half of them
+        # zero, the 99.9th percentile at 127), Gaussian weights quantised per filter to +-127, a rescale that
+        # puts the 99.9th percentile of the accumulator at 127. A 4 Mi block of seeded values repeated to size.
+        g = prng.normal(11, min(n, 1 << 22))
+        base = np.clip(np.rint(np.maximum(g, 0.0) * (127.0 / 3.3)), 0, 127).astype(np.int8)
+        x = np.resize(base, n).reshape(b, c_in, side, side)
+        fan_in = c_in * k * k
+        wf = prng.normal(12, c_out * fan_in).reshape(c_out, fan_in)
+        w = np.clip(np.rint(wf * (127.0 / np.abs(wf).max(axis=1, keepdims=True))), -127, 127).astype(np.int8)
+        del wf, g
+        xm, xv = float(base.mean()), float(base.var())
+        acc_mean = w.astype(np.float64).sum(axis=1) * xm
+        acc_std = np.sqrt((w.astype(np.float64) ** 2).sum(axis=1) * xv)
+        mul, shift = normalise_scale(127.0 / (3.3 * acc_std))
+        bias = (-np.rint(acc_mean)).astype(np.int32)
+        w = w.reshape(c_out, c_in, k, k)
+        iters = max(50, int(0.5e6 / est_us))
+        with ClockSampler(period=0.005) as clk:
+            _, us, tl = iodf.iodf_conv_probe_timeline(x, w, bias, mul, shift, relu=True, iters=iters)
+        ops = 2.0 * b * side * side * c_in * c_out * k * k
+        row = dict(layer="%dx%d %d->%d on %d x %dx%d" % (k, k, c_in, c_out, b, side, side), launches=2 * iters + 2,
+                   us_per_launch=round(us, 2), tops=round(ops / (us * 1e-6) / 1e12, 1),
+                   frac_of_int8_peak=round(ops / (us * 1e-6) / 1e12 / INT8_PEAK_TOPS, 4), engine_clock_mhz=clk.summary())
+        if len(tl):
+            t = tl.astype(np.float64)
+            wall = t[:, 3] - t[:, 0]
+            ok = wall > 0
+            ghz = (t[ok, 5] - t[ok, 4]) / wall[ok] * 0.1
+            med = lambda v: round(float(np.median(v)), 3)
+            row["timeline"] = dict(tiles=int(len(tl)), cu_clock_ghz_median=med(ghz), cu_clock_ghz_min=round(float(ghz.min()), 3),
+                                   cu_clock_ghz_max=round(float(ghz.max()), 3),
+                                   first_operands_wait_us=med((t[:, 1] - t[:, 0]) * 0.01),
+                                   k_loop_us=med((t[:, 2] - t[:, 1]) * 0.01), epilogue_us=med((t[:, 3] - t[:, 2]) * 0.01),
+                                   launch_span_us=round(float((t[:, 3].max() - t[:, 0].min()) * 0.01), 2))
+        rows.append(row)
+    return {"layer_clock": rows, "note": "k loop and epilogue per output tile; counters: s_memrealtime (100 MHz) and s_memtime"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -278,6 +330,9 @@ def main():
                     help="HxW of the synthetic high-resolution image of the patch-coding leg ('' to skip)")
     ap.add_argument("--table1", action="store_true",
                     help="only time the three isolated 3x3 convolution shapes of the paper's Table 1 and exit")
+    ap.add_argument("--layer-clock", action="store_true",
+                    help="only run isolated wide layers of the headline workload back to back, each with the engine "
+                         "clock sampled beside it and a per-tile timeline from inside the kernel, and exit")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain 1 GiB device copy (calibrates HBM byte counters) and exit")
     args = ap.parse_args()
@@ -316,6 +371,10 @@ def main():
                 rows.append(dict(c_in=c_in, c_out=c_out, batch=b, us_per_launch=round(us, 3),
                                  tops=round(ops / (us * 1e-6) / 1e12, 2)))
         print(json.dumps({"table1_conv3x3_16x16_int8": rows, "unit": "microseconds per launch (device time, back-to-back)"}))
+        return
+
+    if args.layer_clock:
+        print(json.dumps(layer_clock(iodf, np)))
         return
 
     cfg = CONFIGS[args.config]

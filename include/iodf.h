@@ -200,6 +200,20 @@ int iodf_conv_probe(int device_ordinal, int c_in, int c_out, int k, int h, int w
                     const uint8_t* shift_host, int8_t* y_host, int iters, float* us_per_call);
 
 /*
+ * iodf_conv_probe plus a per-tile timeline of one more launch that follows `iters` further back-to-back
+ * launches (so it sees the clocks of sustained work). timeline_host: int64 [max_tiles][8], one row per
+ * output tile that ran (*n_tiles rows): [0..3] the constant 100 MHz counter when the tile's workgroup
+ * started on it, when its first k-tile had landed, after its k loop and after its epilogue; [4], [5] the
+ * shader-clock counter at start and end, so (row[5] - row[4]) / (row[3] - row[0]) x 100 MHz is the clock the
+ * compute unit ran at; [6], [7] zero. Split launches (a last layer cut along K) are not traced.
+ * Measurement support for the roofline analysis, not part of the coding path.
+ */
+int iodf_conv_probe_timeline(int device_ordinal, int c_in, int c_out, int k, int h, int w, int batch, int relu,
+                             const int8_t* x_host, const int8_t* w_host, const int32_t* bias_host,
+                             const int32_t* m_host, const uint8_t* shift_host, int8_t* y_host, int iters,
+                             float* us_per_call, int64_t* timeline_host, int max_tiles, int* n_tiles);
+
+/*
  * Per-kernel timing for roofline reports (the paper reports latency only, Sec. 5.2; this is
  * measurement support, not part of the method). Between begin and end every kernel launch of
  * iodf_forward / iodf_inverse is bracketed by HIP events on the caller's stream (no

@@ -24,7 +24,7 @@ IODF_Q_Z_ELEMS, IODF_Q_CODE_BYTES, IODF_Q_WORKSPACE_BYTES, IODF_Q_MACS_FORWARD, 
 EXPORTS = ["iodf_init", "iodf_forward", "iodf_inverse", "iodf_query", "iodf_free", "iodf_strerror",
            "iodf_last_hip_error", "iodf_profile_begin", "iodf_profile_end", "iodf_prior_cf", "iodf_encode",
            "iodf_decode", "iodf_codec_tables", "iodf_tile_patches", "iodf_untile_patches",
-           "iodf_conv_probe", "iodf_encode_noalloc"]
+           "iodf_conv_probe", "iodf_encode_noalloc", "iodf_conv_probe_timeline"]
 
 
 class KernelStat(ctypes.Structure):
@@ -105,6 +105,9 @@ def load_library(build_if_missing=True):
     L.iodf_conv_probe.restype = ci
     L.iodf_conv_probe.argtypes = [ci, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, ci,
                                   ctypes.POINTER(ctypes.c_float)]
+    L.iodf_conv_probe_timeline.restype = ci
+    L.iodf_conv_probe_timeline.argtypes = [ci, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, ci,
+                                           ctypes.POINTER(ctypes.c_float), vp, ci, ctypes.POINTER(ci)]
     L.iodf_tile_patches.restype = ci
     L.iodf_tile_patches.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp]
     L.iodf_untile_patches.restype = ci
@@ -182,6 +185,26 @@ def iodf_conv_probe(x, w, bias, m, shift, relu=True, iters=20, device_ordinal=0)
     _check(load_library().iodf_conv_probe(int(device_ordinal), c_in, c_out, k, h, wd, b, 1 if relu else 0, p(x), p(w),
                                           p(bias), p(m), p(shift), p(y), int(iters), ctypes.byref(us)))
     return y, float(us.value)
+
+
+def iodf_conv_probe_timeline(x, w, bias, m, shift, relu=True, iters=20, max_tiles=4096, device_ordinal=0):
+    """As iodf_conv_probe, plus the per-tile timeline of one more launch: int64 [n_tiles, 8] (see include/iodf.h)."""
+    x = np.ascontiguousarray(x, np.int8)
+    w = np.ascontiguousarray(w, np.int8)
+    bias = np.ascontiguousarray(bias, np.int32)
+    m = np.ascontiguousarray(m, np.int32)
+    shift = np.ascontiguousarray(shift, np.uint8)
+    b, c_in, h, wd = x.shape
+    c_out, c_in2, k, k2 = w.shape
+    assert c_in == c_in2 and k == k2 and bias.size == m.size == shift.size == c_out
+    y = np.zeros((b, c_out, h, wd), np.int8)
+    tl = np.zeros((max_tiles, 8), np.int64)
+    us, n = ctypes.c_float(0), ctypes.c_int(0)
+    p = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+    _check(load_library().iodf_conv_probe_timeline(int(device_ordinal), c_in, c_out, k, h, wd, b, 1 if relu else 0,
+                                                   p(x), p(w), p(bias), p(m), p(shift), p(y), int(iters),
+                                                   ctypes.byref(us), p(tl), int(max_tiles), ctypes.byref(n)))
+    return y, float(us.value), tl[:n.value]
 
 
 def iodf_codec_tables():

@@ -63,6 +63,11 @@ struct ConvArgs {
     // Unsigned codes (0..255, stored as code - 128): out_unsigned saturates MODE_ACT results to [0, 255]
     // (the layer then has a ReLU); sc_unsigned says the shortcut bytes are such codes.
     int out_unsigned, sc_unsigned;
+    // Optional per-tile timeline (measurement support; nullptr = off): the first wave of a workgroup writes,
+    // for the output tile in slot s, trace[8 s + 0..3] = the constant 100 MHz counter at tile start, after its
+    // first k-tile landed, after the k loop and after the epilogue; [4], [5] = the shader-clock counter at
+    // tile start and end. Slots are numbered as blockIdx.x of the plain kernel numbers them.
+    long long* trace;
     int n_cu;      // compute units of the device the layer runs on (conv_device_cus); decides the launch shape
     int log2_w, log2_hw;  // filled by launch_conv: log2 of w and of h*w when both are powers of two, else -1
     int32_t* partial;  // optional split-K scratch: int32 [npix][n_pad], all zero between launches
@@ -93,6 +98,8 @@ hipError_t launch_conv(const ConvArgs& a, hipStream_t stream);
 int conv_pick_tile(const ConvArgs& a);
 int conv_num_tiles();
 const char* conv_tile_name(int tile);
+// Timeline slots launch_conv would use for `a` (see ConvArgs::trace): 8 x int64 each; 0 for invalid arguments.
+int conv_trace_slots(const ConvArgs& a);
 // Channels x pixels of a tile (0, 0 for an invalid index).
 void conv_tile_dims(int tile, int* bc, int* bp);
 // Set-up of kernel attributes (dynamic LDS sizes) on the current device.

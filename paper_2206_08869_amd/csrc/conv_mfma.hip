@@ -345,6 +345,15 @@ __device__ __forceinline__ void wait_tiles_then_barrier() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
+// Timeline of one output tile (see ConvArgs::trace): stamp `which` of slot `slot`.
+__device__ __forceinline__ void trace_stamp(const ConvArgs& a, int slot, int which, int tid) {
+    if (a.trace && tid == 0) {
+        a.trace[8LL * slot + which] = (long long)wall_clock64();
+        if (which == 0) a.trace[8LL * slot + 4] = (long long)clock64();
+        if (which == 3) a.trace[8LL * slot + 5] = (long long)clock64();
+    }
+}
+
 // BC channels x BP pixels per workgroup, WC x WP waves, NST LDS stages of one 64-byte k-tile.
 //
 // Tiles go from global memory straight into LDS (global_load_lds_dwordx4): a wave-wide load
@@ -384,6 +393,7 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
     if (pb >= npb) return;
     const int p0 = pb * BP, c0 = cb * BC;
     if (c0 >= a.n_store) return;  // a channel block of padding only
+    trace_stamp(a, bid, 0, tid);
 
     // split-K: blockIdx.y owns a contiguous range of k-tiles and adds its partial sums to a.partial
     const int nkt_all = a.taps * (a.cin_pad / KT);
@@ -527,6 +537,7 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
         });
     };
     wait_tiles_then_barrier<(NST - 2) * LPT>();  // tile 0 has landed
+    trace_stamp(a, bid, 1, tid);
     read_frags(0, 0, wf0, af0);
     // One step per k-tile. The steps are unrolled NST-fold so that every LDS stage offset is
     // a compile-time constant.
@@ -553,6 +564,7 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
     }
     // drain the tail loads (they target stages nobody reads any more) before the wave retires
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    trace_stamp(a, bid, 2, tid);
 
     if constexpr (EPI == EPI_FAST_RELU)
         conv_epilogue_fast<TC, TP, true>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw, cst, BC, wc * WTC);
@@ -562,6 +574,7 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
         conv_epilogue_partial<TC, TP>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane);
     else
         conv_epilogue<TC, TP>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw);
+    trace_stamp(a, bid, 3, tid);
 }
 
 // Persistent form of conv_igemm for launches with several output tiles per CU (fast epilogues only,
@@ -738,9 +751,11 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm_persist(const ConvArgs
         int p0, c0;
         slot_tile(cur, p0, c0);
         int* const cst = cstbuf + (n & 1) * 4 * BC;
+        trace_stamp(a, cur, 0, tid);
         // k-tile 0 of this output tile and, before it, its constants have landed (first tile: just
         // issued; later tiles: issued during the previous k loop)
         wait_tiles_then_barrier<(NST - 2) * LPT>();
+        trace_stamp(a, cur, 1, tid);
         // accumulators start at the bias (the fast epilogues expect it there)
         static_for<TC>([&](auto tc_) {
             constexpr int tc = decltype(tc_)::value;
@@ -763,10 +778,12 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm_persist(const ConvArgs
             static_assert(NST <= 4, "unrolled for at most four stages");
         }
         const int nxt = next_slot(cur + (int)gridDim.x);
+        trace_stamp(a, cur, 2, tid);
         if constexpr (EPI == EPI_FAST_RELU)
             conv_epilogue_fast<TC, TP, true>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw, cst, BC, wc * WTC);
         else
             conv_epilogue_fast<TC, TP, false>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw, cst, BC, wc * WTC);
+        trace_stamp(a, cur, 3, tid);
         if (nxt >= nslots) break;
         cur = nxt;
     }
@@ -961,6 +978,14 @@ int conv_pick_splits(const ConvArgs& a, int tile) {
     if (s > nkt / 16) s = nkt / 16;
     if (s > 32) s = 32;
     return s < 2 ? 1 : (int)s;
+}
+
+int conv_trace_slots(const ConvArgs& a) {
+    const int best = conv_pick_tile(a);
+    if (best < 0) return 0;
+    const TileCfg& t = kTiles[best == kPersistTile ? 0 : best];
+    const int npb = (a.npix + t.bp - 1) / t.bp, ncb = a.n_pad / t.bc;
+    return ((npb + 7) / 8) * 8 * ncb;
 }
 
 hipError_t launch_conv(const ConvArgs& a_in, hipStream_t stream) {

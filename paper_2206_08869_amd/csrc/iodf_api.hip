@@ -615,7 +615,7 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
     const int npix = batch * h * w;
     const int32_t* phi = (const int32_t*)(ctx->params + N.phi_off);
     const long long plane = ctx->plane[lv];
-    PROF_LAUNCH(ctx, st, CLS_QUANT_IN, 0, (long long)npix * (4 * N.C_in + N.cin_pad0),
+    PROF_LAUNCH(ctx, st, CLS_QUANT_IN, 0, (long long)npix * (4 * N.C_in + (N.C_in + 3) / 4 * 4),
                 launch_quant_in(ctx->state[lv], npix, h, w, N.C, phi, N.C_in, N.M_in, N.s_in, ctx->buf[lv][BUF_XQ],
                                 N.cin_pad0, plane, st));
     for (const DevLayer& L : N.layers) {
@@ -1305,9 +1305,11 @@ int iodf_untile_patches(iodf_ctx* ctx, const uint8_t* x_dev, int first_patch, in
 
 // One integer-only convolution layer on its own (Sec. 4.3, Table 1 times three such shapes): host
 // tensors in, host tensors out, the same packing and kernels as inside a flow.
-int iodf_conv_probe(int device_ordinal, int c_in, int c_out, int k, int h, int w, int batch, int relu,
-                    const int8_t* x_host, const int8_t* w_host, const int32_t* bias_host, const int32_t* m_host,
-                    const uint8_t* shift_host, int8_t* y_host, int iters, float* us_per_call) {
+static int conv_probe_impl(int device_ordinal, int c_in, int c_out, int k, int h, int w, int batch, int relu,
+                           const int8_t* x_host, const int8_t* w_host, const int32_t* bias_host, const int32_t* m_host,
+                           const uint8_t* shift_host, int8_t* y_host, int iters, float* us_per_call,
+                           int64_t* timeline_host, int max_tiles, int* n_tiles) {
+    if (timeline_host && (max_tiles < 1 || !n_tiles)) return IODF_E_ARG;
     if (c_in < 1 || c_out < 1 || (k != 1 && k != 3) || h < 1 || w < 1 || batch < 1 || c_in > 65536 || c_out > 65536 ||
         !x_host || !w_host || !bias_host || !m_host || !shift_host || !y_host || iters < 1)
         return IODF_E_ARG;
@@ -1340,9 +1342,11 @@ int iodf_conv_probe(int device_ordinal, int c_in, int c_out, int k, int h, int w
                         x_host[(((size_t)b * c_in + c) * h + i) * w + j];
     uint8_t* params = nullptr;
     int8_t *din = nullptr, *dout = nullptr;
+    long long* dtrace = nullptr;
     int rc = IODF_OK;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     auto cleanup = [&]() {
+        if (dtrace) (void)hipFree(dtrace);
         if (params) (void)hipFree(params);
         if (din) (void)hipFree(din);
         if (dout) (void)hipFree(dout);
@@ -1362,6 +1366,7 @@ int iodf_conv_probe(int device_ordinal, int c_in, int c_out, int k, int h, int w
     PROBE_TRY(hipMemset(dout, 0, out_bytes));
     ConvArgs a;
     memset(&a, 0, sizeof(a));
+
     a.in = din; a.in_plane = plane; a.cin_pad = cin_pad; a.taps = k * k; a.h = h; a.w = w; a.npix = batch * h * w;
     a.n_cu = n_cu;
     a.wgt = (const int8_t*)(params + D.wgt_off); a.n_pad = n_pad;
@@ -1380,6 +1385,25 @@ int iodf_conv_probe(int device_ordinal, int c_in, int c_out, int k, int h, int w
     PROBE_TRY(hipEventSynchronize(e1));
     float ms = 0.f;
     PROBE_TRY(hipEventElapsedTime(&ms, e0, e1));
+    if (timeline_host) {
+        // once more with the per-tile timeline on, after another run of back-to-back launches so that the
+        // traced launch sees the clocks of sustained work
+        const int slots = conv_trace_slots(a);
+        if (slots < 1) { cleanup(); return IODF_E_ARG; }
+        PROBE_TRY(hipMalloc((void**)&dtrace, 64 * (size_t)slots));
+        PROBE_TRY(hipMemset(dtrace, 0, 64 * (size_t)slots));
+        for (int i = 0; i < iters; ++i) PROBE_TRY(launch_conv(a, nullptr));
+        a.trace = dtrace;
+        PROBE_TRY(launch_conv(a, nullptr));
+        a.trace = nullptr;
+        PROBE_TRY(hipDeviceSynchronize());
+        std::vector<long long> tl(8 * (size_t)slots);
+        PROBE_TRY(hipMemcpy(tl.data(), dtrace, 64 * (size_t)slots, hipMemcpyDeviceToHost));
+        int n = 0;
+        for (int sl = 0; sl < slots && n < max_tiles; ++sl)
+            if (tl[8 * (size_t)sl + 3]) { memcpy(timeline_host + 8 * (size_t)n, &tl[8 * (size_t)sl], 64); ++n; }
+        *n_tiles = n;
+    }
 #undef PROBE_TRY
     if (us_per_call) *us_per_call = 1e3f * ms / (float)iters;
     for (int b = 0; b < batch; ++b)
@@ -1390,6 +1414,22 @@ int iodf_conv_probe(int device_ordinal, int c_in, int c_out, int k, int h, int w
                         yout[(size_t)(c / 64) * plane + ((size_t)b * pp + (size_t)(i + 1) * (w + 2) + (j + 1)) * 64 + c % 64];
     cleanup();
     return rc;
+}
+
+int iodf_conv_probe(int device_ordinal, int c_in, int c_out, int k, int h, int w, int batch, int relu,
+                    const int8_t* x_host, const int8_t* w_host, const int32_t* bias_host, const int32_t* m_host,
+                    const uint8_t* shift_host, int8_t* y_host, int iters, float* us_per_call) {
+    return conv_probe_impl(device_ordinal, c_in, c_out, k, h, w, batch, relu, x_host, w_host, bias_host, m_host,
+                           shift_host, y_host, iters, us_per_call, nullptr, 0, nullptr);
+}
+
+int iodf_conv_probe_timeline(int device_ordinal, int c_in, int c_out, int k, int h, int w, int batch, int relu,
+                             const int8_t* x_host, const int8_t* w_host, const int32_t* bias_host,
+                             const int32_t* m_host, const uint8_t* shift_host, int8_t* y_host, int iters,
+                             float* us_per_call, int64_t* timeline_host, int max_tiles, int* n_tiles) {
+    if (!timeline_host) return IODF_E_ARG;
+    return conv_probe_impl(device_ordinal, c_in, c_out, k, h, w, batch, relu, x_host, w_host, bias_host, m_host,
+                           shift_host, y_host, iters, us_per_call, timeline_host, max_tiles, n_tiles);
 }
 
 int iodf_profile_begin(iodf_ctx* ctx, int max_launches) {

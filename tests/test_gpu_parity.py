@@ -245,6 +245,17 @@ def test_single_convolution_on_many_pixels_matches_oracle(c_in, c_out, k, b, sid
     _check_single_convolution(c_in, c_out, k, True, 36, b, side, side)
 
 
+@pytest.mark.parametrize("c_in,c_out,k,relu,b,side", [
+    (256, 256, 3, True, 1, 32),     # 64 tiles of 64x64, 36 k-tiles
+    (2304, 256, 1, True, 1, 8),     # 4 tiles, 36 k-tiles
+    (1920, 256, 1, False, 3, 4),    # 30 k-tiles, 48 pixels (ragged tile), no ReLU
+    (512, 512, 3, True, 2, 4),      # 72 k-tiles, 32 pixels: half a pixel tile
+])
+def test_single_convolution_on_few_pixels_matches_oracle(c_in, c_out, k, relu, b, side):
+    """Hidden layers as a batch-1 call sees them: a handful of small tiles, long reductions."""
+    _check_single_convolution(c_in, c_out, k, relu, 36, b, side, side)
+
+
 def _check_single_convolution(c_in, c_out, k, relu, shift_lo, b, h, w):
     import oracle
     rng = np.random.default_rng(c_in * 1000 + c_out)
