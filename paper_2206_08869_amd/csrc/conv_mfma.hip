@@ -503,8 +503,47 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
         ikx = go ? ((wrap || row) ? 0 : ikx + 1) : ikx;
     };
 
+    // Small wave tiles (one or two MFMAs per k-step) run at the pace of the wave's instruction stream, not
+    // of the matrix pipe: one wave per SIMD issues about fifty instructions per k-tile in the general loop,
+    // most of them the scalar bookkeeping that finds the next tile. The lean loop below does that
+    // bookkeeping at compile time: a ring of nine stages and nine unrolled steps, so that both the LDS
+    // stage and the filter tap of every load and of every fragment read are constants and a tap's address
+    // is the plane pointer plus a loop-invariant scalar.
+    constexpr bool LEAN = TC * TP <= 2 && NST == 9;
+    const bool lean = LEAN && nsk == 1;
+    const int8_t* lw = wbase;                                                      // weight k-tile to load next
+    const int8_t* la = abase + (a.taps == 9 ? (long long)(-W2 - 1) * KT : 0LL);     // pixel (i-1, j-1) of the plane to load next
+    const long long rowstep = (long long)W2 * KT;
+    int lissued = 0;
+    [[maybe_unused]] auto lean_issue = [&](auto stage_, auto tap_, auto taps_) {
+        constexpr int stage = decltype(stage_)::value, tap = decltype(tap_)::value, taps = decltype(taps_)::value;
+        unsigned char* sb = lds + stage * STAGE;
+        const int8_t* wu = uniform(lw);
 #pragma unroll
-    for (int t = 0; t < NST - 1; ++t) issue();
+        for (int u = 0; u < WI; ++u)
+            __builtin_amdgcn_global_load_lds((gptr_t)(wu + u * 1024 + woffl), (lptr_t)(sb + (wave * WI + u) * 1024), 16,
+                                             0, 0);
+        // (the load's immediate offset would shift the LDS address as well, so the tap's offset is added to the pointer)
+        const int8_t* au = uniform(la + (taps == 9 ? (tap / 3) * rowstep + (tap % 3) * KT : 0LL));
+#pragma unroll
+        for (int u = 0; u < AI; ++u)
+            __builtin_amdgcn_global_load_lds((gptr_t)(au + aoffl[u]), (lptr_t)(sb + BC * KT + (wave * AI + u) * 1024),
+                                             16, 0, 0);
+        // past the last k-tile the pointers stay (the same tile lands again in a stage nobody reads)
+        ++lissued;
+        const bool go = lissued < nkt;
+        lw += go ? wtile : 0LL;
+        if constexpr (taps == 1 || tap == 8) la += go ? a.in_plane : 0LL;
+    };
+    if (lean) {
+        if (a.taps == 9)
+            static_for<NST - 1>([&](auto t_) { lean_issue(t_, t_, std::integral_constant<int, 9>{}); });
+        else
+            static_for<NST - 1>([&](auto t_) { lean_issue(t_, std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{}); });
+    } else {
+#pragma unroll
+        for (int t = 0; t < NST - 1; ++t) issue();
+    }
     if (tid < BC) {
         cst[tid] = cb_v;
         cst[BC + tid] = cm_v;
@@ -538,6 +577,70 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
     };
     wait_tiles_then_barrier<(NST - 2) * LPT>();  // tile 0 has landed
     trace_stamp(a, bid, 1, tid);
+    if (lean) {
+        if constexpr (LEAN) {
+            // Fragments of a whole k-tile are read two k-tiles ahead into three rotating register sets, the
+            // two k-steps add into separate accumulators (no dependent MFMAs back to back; the integer sums
+            // are merged at the end), and the barrier only asks for the LDS reads issued before the previous
+            // barrier: no LDS latency is left on the path from one k-tile to the next.
+            constexpr int FR = 2 * (TC + TP);
+            v4i fw[3][2][TC], fa[3][2][TP];
+            v16i acc1[TC][TP];
+            static_for<TC>([&](auto tc_) {
+                static_for<TP>([&](auto tp_) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc1[decltype(tc_)::value][decltype(tp_)::value][r] = 0;
+                });
+            });
+            auto read_tile = [&](int stage, auto set_) {
+                constexpr int set = decltype(set_)::value;
+                read_frags(stage, 0, fw[set][0], fa[set][0]);
+                read_frags(stage, 1, fw[set][1], fa[set][1]);
+            };
+            auto mma_tile = [&](auto set_) {
+                constexpr int set = decltype(set_)::value;
+                static_for<TC>([&](auto tc_) {
+                    constexpr int tc = decltype(tc_)::value;
+                    static_for<TP>([&](auto tp_) {
+                        constexpr int tp = decltype(tp_)::value;
+                        acc[tc][tp] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[set][0][tc], fa[set][0][tp], acc[tc][tp], 0, 0, 0);
+                        acc1[tc][tp] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[set][1][tc], fa[set][1][tp], acc1[tc][tp], 0, 0, 0);
+                    });
+                });
+            };
+            auto lean_loop = [&](auto taps_) {
+                constexpr int taps = decltype(taps_)::value;
+                read_tile(0, std::integral_constant<int, 0>{});
+                wait_tiles_then_barrier<(NST - 3) * LPT>();  // tile 1 has landed (a repeat of tile 0 when there is only one)
+                read_tile(1, std::integral_constant<int, 1>{});
+                for (int kt = 0; kt < nkt; kt += NST) {
+                    const int left = nkt - kt;
+                    static_for<NST>([&](auto i_) {
+                        constexpr int i = decltype(i_)::value;
+                        if (left > i) {
+                            // tile kt+i+NST-1 goes into the stage of tile kt+i-1; its tap is (i + 8) mod 9
+                            lean_issue(std::integral_constant<int, (i + NST - 1) % NST>{},
+                                       std::integral_constant<int, taps == 9 ? (i + 8) % 9 : 0>{}, taps_);
+                            // tile kt+i+2 has landed; of this wave's LDS reads only the newest k-tile's may be pending
+                            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(%1)\n\ts_barrier" ::"n"((NST - 3) * LPT), "n"(FR) : "memory");
+                            read_tile((i + 2) % NST, std::integral_constant<int, (i + 2) % 3>{});
+                            mma_tile(std::integral_constant<int, i % 3>{});
+                        }
+                    });
+                }
+            };
+            if (a.taps == 9) lean_loop(std::integral_constant<int, 9>{});
+            else lean_loop(std::integral_constant<int, 1>{});
+            static_for<TC>([&](auto tc_) {
+                constexpr int tc = decltype(tc_)::value;
+                static_for<TP>([&](auto tp_) {
+                    constexpr int tp = decltype(tp_)::value;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[tc][tp][r] += acc1[tc][tp][r];
+                });
+            });
+        }
+    } else {
     read_frags(0, 0, wf0, af0);
     // One step per k-tile. The steps are unrolled NST-fold so that every LDS stage offset is
     // a compile-time constant.
@@ -554,16 +657,12 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
     };
     for (int kt = 0; kt < nkt; kt += NST) {
         const int left = nkt - kt;
-        step(std::integral_constant<int, 0>{});
-        if (left > 1) step(std::integral_constant<int, 1>{});
-        if (left > 2) step(std::integral_constant<int, 2>{});
-        if constexpr (NST > 3) {
-            if (left > 3) step(std::integral_constant<int, 3>{});
-        }
-        static_assert(NST <= 4, "unrolled for at most four stages");
+        static_for<NST>([&](auto i_) {
+            constexpr int i = decltype(i_)::value;
+            if (left > i) step(std::integral_constant<int, i>{});
+        });
     }
-    // drain the tail loads (they target stages nobody reads any more) before the wave retires
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
     trace_stamp(a, bid, 2, tid);
 
     if constexpr (EPI == EPI_FAST_RELU)
@@ -574,11 +673,14 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
         conv_epilogue_partial<TC, TP>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane);
     else
         conv_epilogue<TC, TP>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw);
+    // The loads issued past the last k-tile target stages nobody reads any more, but they must have landed
+    // before the wave retires and its LDS goes to another workgroup; they do so while the epilogue runs.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     trace_stamp(a, bid, 3, tid);
 }
 
 // Persistent form of conv_igemm for launches with several output tiles per CU (fast epilogues only,
-// no split-K, a k-tile count that is a multiple of NST). One workgroup per CU walks the tiles
+// no split-K, a k-tile count that is a multiple of NST x taps). One workgroup per CU walks the tiles
 // blockIdx.x, blockIdx.x + gridDim.x, ... The stream of k-tiles runs on across output tiles: once
 // the last k-tile of a tile has been issued the load pointers move to the workgroup's next tile, so
 // the loads that conv_igemm spends on dead stages at the end of its k loop fetch the first k-tiles
@@ -606,7 +708,7 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm_persist(const ConvArgs
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wc = wave % WC, wp = wave / WC;
-    const int nkt = a.taps * (a.cin_pad / KT);  // a multiple of NST (the launcher checks)
+    const int nkt = a.taps * (a.cin_pad / KT);  // a multiple of NST, and of 9 * NST for 3x3 layers (the launcher checks)
     const long long wtile = (long long)a.n_pad * KT;
     const int hw = a.h * a.w;
     const int W2 = a.w + 2, PP = (a.h + 2) * W2;
@@ -632,7 +734,6 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm_persist(const ConvArgs
     const int lrow = lane >> 2;
     const int lpart = (lane & 3) ^ ((lane >> 4) & 3);
     const unsigned woffl = (unsigned)(lrow * KT + lpart * 16);
-    const long long next_plane = a.in_plane - (a.taps == 9 ? (long long)(2 * W2 + 2) * KT : 0LL);
     const int8_t* const abase = a.in + (long long)a.in_chunk0 * a.in_plane;
 
     typedef const void __attribute__((address_space(1))) * gptr_t;
@@ -640,8 +741,6 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm_persist(const ConvArgs
     unsigned aoffl[AI];
     const int8_t* wt;
     const int8_t* at;
-    int itile, itap, ikx;
-    int gi = 0;            // k-tiles issued so far: stage = gi % NST
     int ld_slot, nx_slot;  // slot being loaded, next slot to load
     auto load_setup = [&](int s) {
         int p0, c0;
@@ -652,9 +751,6 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm_persist(const ConvArgs
             m = m < a.npix ? m : a.npix - 1;
             aoffl[u] = (unsigned)bordered_pos(a, m, hw, W2, PP) * KT + (unsigned)(lpart * 16);
         }
-        itile = 0;
-        itap = 0;
-        ikx = 0;
         wt = a.wgt + (long long)(c0 + wave * WI * 16) * KT;
         at = abase + (a.taps == 9 ? (long long)(-W2 - 1) * KT : 0LL);  // tap (0, 0) reads pixel (i - 1, j - 1)
         ld_slot = s;
@@ -678,35 +774,6 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm_persist(const ConvArgs
             __builtin_amdgcn_global_load_lds((gptr_t)(src + lane * 16), (lptr_t)(cstbuf + ((ctile & 1) * 4 + wave) * BC), 16, 0, 0);
         }
         ++ctile;
-    };
-    auto issue = [&]() {
-        unsigned char* sb = lds + (gi % NST) * STAGE;
-        const int8_t* wu = uniform(wt);
-        const int8_t* au = uniform(at);
-#pragma unroll
-        for (int u = 0; u < WI; ++u)
-            __builtin_amdgcn_global_load_lds((gptr_t)(wu + u * 1024 + woffl), (lptr_t)(sb + (wave * WI + u) * 1024), 16,
-                                             0, 0);
-#pragma unroll
-        for (int u = 0; u < AI; ++u)
-            __builtin_amdgcn_global_load_lds((gptr_t)(au + aoffl[u]), (lptr_t)(sb + BC * KT + (wave * AI + u) * 1024),
-                                             16, 0, 0);
-        ++gi;
-        if (++itile == nkt) {
-            // once per output tile: on to this workgroup's next slot; after the last one the same tile
-            // is loaded again into stages nobody reads, which keeps the loads per step constant
-            const int s = nx_slot < nslots ? nx_slot : ld_slot;
-            if (nx_slot < nslots) nx_slot = next_slot(nx_slot + (int)gridDim.x);
-            load_setup(s);
-            load_consts(s);
-        } else {
-            const bool wrap = itap + 1 == a.taps;
-            const bool row = ikx == 2;
-            wt += wtile;
-            at += wrap ? next_plane : (long long)((row ? W2 - 2 : 1) * KT);
-            itap = wrap ? 0 : itap + 1;
-            ikx = (wrap || row) ? 0 : ikx + 1;
-        }
     };
     load_setup(cur);
     load_consts(cur);
@@ -735,58 +802,100 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm_persist(const ConvArgs
             });
         });
     };
-    auto step = [&](auto st_) {
-        constexpr int st = decltype(st_)::value;
-        read_frags(st, 1, wf1, af1);
-        mma(wf0, af0);
-        issue();
-        wait_tiles_then_barrier<(NST - 2) * LPT>();
-        read_frags((st + 1) % NST, 0, wf0, af0);
-        mma(wf1, af1);
-    };
 
+    // The k loop is unrolled over both the ring (NST stages) and the filter taps, U = lcm(NST, taps) steps, so
+    // that the LDS stage and the tap of every load are compile-time constants and a step has no branch:
+    // a tap's address is the plane pointer plus a loop-invariant scalar, the weights advance by one k-tile,
+    // the plane pointer moves on after tap 8. The switch to the workgroup's next output tile (a division or
+    // two, the constants' loads) happens at one fixed step of the last round, NST - 1 steps before the end,
+    // which is where the load stream crosses into the next tile. With the bookkeeping out of the way the
+    // compiler spreads the remaining scalar instructions between the MFMAs instead of leaving them as one
+    // block between the last MFMA and the barrier, where both waves of a SIMD used to execute them at the
+    // same time with the matrix pipe idle.
+    const long long rowstep = (long long)W2 * KT;
+    auto issue_static = [&](auto stage_, auto tap_, auto taps_) {
+        constexpr int stage = decltype(stage_)::value, tap = decltype(tap_)::value, taps = decltype(taps_)::value;
+        unsigned char* sb = lds + stage * STAGE;
+        const int8_t* wu = uniform(wt);
 #pragma unroll
-    for (int t = 0; t < NST - 1; ++t) issue();
-    for (int n = 0;; ++n) {
-        int p0, c0;
-        slot_tile(cur, p0, c0);
-        int* const cst = cstbuf + (n & 1) * 4 * BC;
-        trace_stamp(a, cur, 0, tid);
-        // k-tile 0 of this output tile and, before it, its constants have landed (first tile: just
-        // issued; later tiles: issued during the previous k loop)
-        wait_tiles_then_barrier<(NST - 2) * LPT>();
-        trace_stamp(a, cur, 1, tid);
-        // accumulators start at the bias (the fast epilogues expect it there)
-        static_for<TC>([&](auto tc_) {
-            constexpr int tc = decltype(tc_)::value;
+        for (int u = 0; u < WI; ++u)
+            __builtin_amdgcn_global_load_lds((gptr_t)(wu + u * 1024 + woffl), (lptr_t)(sb + (wave * WI + u) * 1024), 16,
+                                             0, 0);
+        // (the load's immediate offset would shift the LDS address as well, so the tap's offset joins the pointer)
+        const int8_t* au = uniform(at + (taps == 9 ? (tap / 3) * rowstep + (tap % 3) * KT : 0LL));
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const v4i b4 = *(const v4i*)(cst + 3 * BC + wc * WTC + tc * 32 + g * 8 + half * 4);
-                static_for<TP>([&](auto tp_) {
-                    constexpr int tp = decltype(tp_)::value;
+        for (int u = 0; u < AI; ++u)
+            __builtin_amdgcn_global_load_lds((gptr_t)(au + aoffl[u]), (lptr_t)(sb + BC * KT + (wave * AI + u) * 1024),
+                                             16, 0, 0);
+        wt += wtile;
+        if constexpr (taps == 1 || tap == 8) at += a.in_plane;
+    };
+    // once per output tile: on to this workgroup's next slot; after the last one the same tile is loaded
+    // again into stages nobody reads, which keeps the loads per step constant and every address valid
+    auto switch_tile = [&]() {
+        const int s = nx_slot < nslots ? nx_slot : ld_slot;
+        if (nx_slot < nslots) nx_slot = next_slot(nx_slot + (int)gridDim.x);
+        load_setup(s);
+        load_consts(s);
+    };
+    auto run = [&](auto taps_) {
+        constexpr int taps = decltype(taps_)::value;
+        constexpr int U = taps == 9 ? 9 * NST : NST;   // nkt is a multiple of U (the launcher checks)
+        static_for<NST - 1>([&](auto t_) { issue_static(t_, std::integral_constant<int, taps == 9 ? decltype(t_)::value : 0>{}, taps_); });
+        for (int n = 0;; ++n) {
+            int p0, c0;
+            slot_tile(cur, p0, c0);
+            int* const cst = cstbuf + (n & 1) * 4 * BC;
+            trace_stamp(a, cur, 0, tid);
+            // k-tile 0 of this output tile and, before it, its constants have landed (first tile: just
+            // issued; later tiles: issued during the previous k loop)
+            wait_tiles_then_barrier<(NST - 2) * LPT>();
+            trace_stamp(a, cur, 1, tid);
+            // accumulators start at the bias (the fast epilogues expect it there)
+            static_for<TC>([&](auto tc_) {
+                constexpr int tc = decltype(tc_)::value;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[tc][tp][g * 4 + e] = b4[e];
+                for (int g = 0; g < 4; ++g) {
+                    const v4i b4 = *(const v4i*)(cst + 3 * BC + wc * WTC + tc * 32 + g * 8 + half * 4);
+                    static_for<TP>([&](auto tp_) {
+                        constexpr int tp = decltype(tp_)::value;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[tc][tp][g * 4 + e] = b4[e];
+                    });
+                }
+            });
+            read_frags(0, 0, wf0, af0);
+            for (int kt = 0; kt < nkt; kt += U) {
+                static_for<U>([&](auto i_) {
+                    constexpr int i = decltype(i_)::value;
+                    constexpr int st = i % NST;
+                    read_frags(st, 1, wf1, af1);
+                    mma(wf0, af0);
+                    // k-tile kt + i + NST - 1 of the load stream goes into the stage of k-tile kt + i - 1;
+                    // in the last round that stream reaches the end of this output tile at step U - NST + 1
+                    if constexpr (i == U - NST + 1) {
+                        if (kt + U >= nkt) switch_tile();
+                    }
+                    issue_static(std::integral_constant<int, (i + NST - 1) % NST>{},
+                                 std::integral_constant<int, taps == 9 ? (i + NST - 1) % 9 : 0>{}, taps_);
+                    wait_tiles_then_barrier<(NST - 2) * LPT>();
+                    read_frags((st + 1) % NST, 0, wf0, af0);
+                    mma(wf1, af1);
                 });
             }
-        });
-        read_frags(0, 0, wf0, af0);
-        for (int kt = 0; kt < nkt; kt += NST) {
-            step(std::integral_constant<int, 0>{});
-            step(std::integral_constant<int, 1>{});
-            step(std::integral_constant<int, 2>{});
-            if constexpr (NST > 3) step(std::integral_constant<int, 3>{});
-            static_assert(NST <= 4, "unrolled for at most four stages");
+            const int nxt = next_slot(cur + (int)gridDim.x);
+            trace_stamp(a, cur, 2, tid);
+            if constexpr (EPI == EPI_FAST_RELU)
+                conv_epilogue_fast<TC, TP, true>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw, cst, BC, wc * WTC);
+            else
+                conv_epilogue_fast<TC, TP, false>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw, cst, BC, wc * WTC);
+            trace_stamp(a, cur, 3, tid);
+            if (nxt >= nslots) break;
+            cur = nxt;
         }
-        const int nxt = next_slot(cur + (int)gridDim.x);
-        trace_stamp(a, cur, 2, tid);
-        if constexpr (EPI == EPI_FAST_RELU)
-            conv_epilogue_fast<TC, TP, true>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw, cst, BC, wc * WTC);
-        else
-            conv_epilogue_fast<TC, TP, false>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw, cst, BC, wc * WTC);
-        trace_stamp(a, cur, 3, tid);
-        if (nxt >= nslots) break;
-        cur = nxt;
-    }
+    };
+    if (a.taps == 9) run(std::integral_constant<int, 9>{});
+    else run(std::integral_constant<int, 1>{});
     // drain the tail loads (they target stages nobody reads any more) before the wave retires
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
@@ -845,7 +954,7 @@ const TileCfg kTiles[] = {
     IODF_TILE(128, 512, 2, 4, 3),
     IODF_TILE(128, 128, 4, 2, 4),
     IODF_TILE(64, 256, 1, 4, 4),
-    IODF_TILE(64, 64, 2, 2, 4),
+    IODF_TILE(64, 64, 2, 2, 9),
     // four-wave halves of the first two tiles: 72 KB of LDS and at most 256 registers, so two
     // workgroups share a CU (see conv_pick_tile)
     IODF_TILE(256, 128, 2, 2, 3),
@@ -926,10 +1035,11 @@ int pick_epi(const ConvArgs& a) {
 }
 
 // Whether the 256x256 tile runs in its persistent form: two or more tiles per CU, a fast epilogue
-// and whole rounds of the stage ring.
+// and a k-tile count that is a whole number of the kernel's unrolled rounds (ring stages x taps).
 bool persist_ok(const ConvArgs& a, long long tiles) {
     const int nkt = a.taps * (a.cin_pad / KT);
-    return pick_epi(a) != EPI_ANY && nkt % 4 == 0 && persist_grid(a) >= 8 && tiles >= 2LL * persist_grid(a);
+    return pick_epi(a) != EPI_ANY && nkt % (a.taps == 9 ? 36 : 4) == 0 && persist_grid(a) >= 8 &&
+           tiles >= 2LL * persist_grid(a);
 }
 
 // First tile in table order that still fills the chip (its two-per-CU half when the reduction is
