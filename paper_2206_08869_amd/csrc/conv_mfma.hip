@@ -503,14 +503,18 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
         ikx = go ? ((wrap || row) ? 0 : ikx + 1) : ikx;
     };
 
-    // Small wave tiles (one or two MFMAs per k-step) run at the pace of the wave's instruction stream, not
-    // of the matrix pipe: one wave per SIMD issues about fifty instructions per k-tile in the general loop,
-    // most of them the scalar bookkeeping that finds the next tile. The lean loop below does that
-    // bookkeeping at compile time: a ring of nine stages and nine unrolled steps, so that both the LDS
-    // stage and the filter tap of every load and of every fragment read are constants and a tap's address
-    // is the plane pointer plus a loop-invariant scalar.
-    constexpr bool LEAN = TC * TP <= 2 && NST == 9;
-    const bool lean = LEAN && nsk == 1;
+    // The bookkeeping that finds the next k-tile (which tap, which kernel row, which plane, which ring
+    // stage) costs the general issue() above some twenty-five scalar instructions and a branch or two per
+    // k-tile, and the compiler leaves them as one block between the last MFMA of a step and the barrier. The
+    // lean loops below do it at compile time: they are unrolled over lcm(ring stages, 9 taps) steps, so the
+    // LDS stage and the tap of every load and fragment read are constants, a tap's address is the plane
+    // pointer plus a loop-invariant scalar, and a step has no branch. Launches whose reduction is not split
+    // (every hidden layer) take them; the general loop remains for split reductions, which start mid-plane.
+    // Small wave tiles (one or two MFMAs per k-step) additionally run at the pace of the wave's instruction
+    // stream and of the LDS latency, not of the matrix pipe: they get a ring of nine stages and read their
+    // fragments two k-tiles ahead (see below).
+    constexpr bool SMALL = TC * TP <= 2 && NST == 9;
+    const bool lean = EPI != EPI_ANY || nsk == 1;
     const int8_t* lw = wbase;                                                      // weight k-tile to load next
     const int8_t* la = abase + (a.taps == 9 ? (long long)(-W2 - 1) * KT : 0LL);     // pixel (i-1, j-1) of the plane to load next
     const long long rowstep = (long long)W2 * KT;
@@ -540,7 +544,7 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
             static_for<NST - 1>([&](auto t_) { lean_issue(t_, t_, std::integral_constant<int, 9>{}); });
         else
             static_for<NST - 1>([&](auto t_) { lean_issue(t_, std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{}); });
-    } else {
+    } else if constexpr (EPI == EPI_ANY) {
 #pragma unroll
         for (int t = 0; t < NST - 1; ++t) issue();
     }
@@ -578,7 +582,33 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
     wait_tiles_then_barrier<(NST - 2) * LPT>();  // tile 0 has landed
     trace_stamp(a, bid, 1, tid);
     if (lean) {
-        if constexpr (LEAN) {
+        if constexpr (!SMALL) {
+            auto big_loop = [&](auto taps_) {
+                constexpr int taps = decltype(taps_)::value;
+                constexpr int U = taps == 1 ? NST : NST % 9 == 0 ? NST : NST % 3 == 0 ? 3 * NST : 9 * NST;  // lcm(NST, taps)
+                read_frags(0, 0, wf0, af0);
+                for (int kt = 0; kt < nkt; kt += U) {
+                    const int left = nkt - kt;
+                    static_for<U>([&](auto i_) {
+                        constexpr int i = decltype(i_)::value;
+                        constexpr int st = i % NST;
+                        if (left > i) {
+                            read_frags(st, 1, wf1, af1);
+                            mma(wf0, af0);
+                            // everybody is past its reads of tile kt+i-1 (they returned before the last barrier), so
+                            // its stage takes tile kt+i+NST-1; then wait until tile kt+i+1 has landed for everybody
+                            lean_issue(std::integral_constant<int, (i + NST - 1) % NST>{},
+                                       std::integral_constant<int, taps == 9 ? (i + NST - 1) % 9 : 0>{}, taps_);
+                            wait_tiles_then_barrier<(NST - 2) * LPT>();
+                            read_frags((st + 1) % NST, 0, wf0, af0);
+                            mma(wf1, af1);
+                        }
+                    });
+                }
+            };
+            if (a.taps == 9) big_loop(std::integral_constant<int, 9>{});
+            else big_loop(std::integral_constant<int, 1>{});
+        } else {
             // Fragments of a whole k-tile are read two k-tiles ahead into three rotating register sets, the
             // two k-steps add into separate accumulators (no dependent MFMAs back to back; the integer sums
             // are merged at the end), and the barrier only asks for the LDS reads issued before the previous
@@ -640,28 +670,25 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
                 });
             });
         }
-    } else {
-    read_frags(0, 0, wf0, af0);
-    // One step per k-tile. The steps are unrolled NST-fold so that every LDS stage offset is
-    // a compile-time constant.
-    auto step = [&](auto st_) {
-        constexpr int st = decltype(st_)::value;
-        read_frags(st, 1, wf1, af1);
-        mma(wf0, af0);
-        // Everybody is past its reads of tile kt-1 (they returned before the last barrier), so
-        // its stage can take tile kt+NST-1; then wait until tile kt+1 has landed for everybody.
-        issue();
-        wait_tiles_then_barrier<(NST - 2) * LPT>();
-        read_frags((st + 1) % NST, 0, wf0, af0);
-        mma(wf1, af1);
-    };
-    for (int kt = 0; kt < nkt; kt += NST) {
-        const int left = nkt - kt;
-        static_for<NST>([&](auto i_) {
-            constexpr int i = decltype(i_)::value;
-            if (left > i) step(std::integral_constant<int, i>{});
-        });
-    }
+    } else if constexpr (EPI == EPI_ANY) {
+        read_frags(0, 0, wf0, af0);
+        // One step per k-tile, unrolled NST-fold so that every LDS stage offset is a compile-time constant.
+        auto step = [&](auto st_) {
+            constexpr int st = decltype(st_)::value;
+            read_frags(st, 1, wf1, af1);
+            mma(wf0, af0);
+            issue();
+            wait_tiles_then_barrier<(NST - 2) * LPT>();
+            read_frags((st + 1) % NST, 0, wf0, af0);
+            mma(wf1, af1);
+        };
+        for (int kt = 0; kt < nkt; kt += NST) {
+            const int left = nkt - kt;
+            static_for<NST>([&](auto i_) {
+                constexpr int i = decltype(i_)::value;
+                if (left > i) step(std::integral_constant<int, i>{});
+            });
+        }
     }
     trace_stamp(a, bid, 2, tid);
 
