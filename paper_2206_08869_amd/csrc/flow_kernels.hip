@@ -84,46 +84,104 @@ __global__ void k_quant_in(const int32_t* __restrict__ S, int npix, int h, int w
     }
 }
 
-// Split after the last coupling of a level. Logical channel c lives at physical phi[c].
-// c >= c_keep: emitted into z (channel-first chunk). c < c_keep: squeezed into the next level.
-__global__ void k_factor_out(const int32_t* __restrict__ S, int B, int h, int w, int C, const int32_t* __restrict__ phi,
-                             int c_keep, int32_t* __restrict__ z, long long d, long long zoff,
-                             int32_t* __restrict__ Snext) {
-    const long long n = (long long)B * C * h * w;
-    for (long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x; t < n; t += (long long)gridDim.x * blockDim.x) {
-        const int j = (int)(t % w);
-        const int i = (int)((t / w) % h);
-        const int c = (int)((t / ((long long)w * h)) % C);
-        const int b = (int)(t / ((long long)w * h * C));
-        const int v = S[(((long long)b * h + i) * w + j) * C + phi[c]];
-        if (c >= c_keep) {
-            z[(long long)b * d + zoff + ((long long)(c - c_keep) * h + i) * w + j] = v;
-        } else {
-            const int h2 = h / 2, w2 = w / 2;
-            Snext[(((long long)b * h2 + i / 2) * w2 + j / 2) * (4 * c_keep) + 4 * c + 2 * (i & 1) + (j & 1)] = v;
+// Split after the last coupling of a level (factor-out fused with the next level's squeeze). Logical
+// channel c lives at physical phi[c]. c >= c_keep: emitted into z (channel-first chunk). c < c_keep:
+// squeezed into the next level, Snext[b][i/2][j/2][4c + 2(i&1) + (j&1)].
+//
+// The state is pixel-major and both outputs are not, so a direct copy is strided on one side. A workgroup
+// instead takes a tile of two image rows x jw columns through LDS: it reads the tile's 2 * jw * C words as two
+// contiguous runs, then writes z in runs of jw words per (channel, row) and the next level's pixels, each
+// 4 * c_keep contiguous words that two rows and two columns of this level make up, in one contiguous run
+// per tile. Rows of the LDS tile are padded by one word so that a column walk does not stay on one bank.
+struct SplitGeom {
+    int B, h, w, C, c_keep, jw, tiles_j, tiles_i;
+    long long d, zoff;
+};
+
+__device__ __forceinline__ void split_tile(const SplitGeom& g, long long tile, int& b, int& i0, int& j0, int& rows, int& cols) {
+    const int tj = (int)(tile % g.tiles_j);
+    const long long q = tile / g.tiles_j;
+    const int ti = (int)(q % g.tiles_i);
+    b = (int)(q / g.tiles_i);
+    i0 = 2 * ti;
+    j0 = tj * g.jw;
+    rows = g.h - i0 < 2 ? g.h - i0 : 2;
+    cols = g.w - j0 < g.jw ? g.w - j0 : g.jw;
+}
+
+__global__ __launch_bounds__(TPB) void k_factor_out(const int32_t* __restrict__ S, const SplitGeom g,
+                                                    const int32_t* __restrict__ phi, int32_t* __restrict__ z,
+                                                    int32_t* __restrict__ Snext) {
+    extern __shared__ int32_t tile_lds[];  // [2][jw][C + 1]
+    const int C = g.C, C1 = C + 1;
+    const long long ntiles = (long long)g.B * g.tiles_i * g.tiles_j;
+    for (long long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        int b, i0, j0, rows, cols;
+        split_tile(g, tile, b, i0, j0, rows, cols);
+        const int run = cols * C;
+        for (int t = threadIdx.x; t < rows * run; t += TPB) {
+            const int rr = t / run, rem = t - rr * run;
+            const int jj = rem / C, pc = rem - jj * C;
+            tile_lds[(rr * g.jw + jj) * C1 + pc] = S[(((long long)b * g.h + i0 + rr) * g.w + j0) * C + rem];
         }
+        __syncthreads();
+        // emitted channels: runs of `cols` words per (channel, row)
+        const int ce = C - g.c_keep;
+        for (int t = threadIdx.x; t < ce * rows * cols; t += TPB) {
+            const int jj = t % cols, q = t / cols;
+            const int rr = q % rows, c = q / rows;
+            z[(long long)b * g.d + g.zoff + ((long long)c * g.h + i0 + rr) * g.w + j0 + jj] =
+                tile_lds[(rr * g.jw + jj) * C1 + phi[g.c_keep + c]];
+        }
+        // kept channels: next-level pixel (i0/2, (j0+jj)/2) holds 4*c_keep consecutive words
+        if (g.c_keep > 0) {
+            const int per = 4 * g.c_keep, npx = cols / 2;
+            int32_t* dst = Snext + (((long long)b * (g.h / 2) + i0 / 2) * (g.w / 2) + j0 / 2) * per;
+            for (int t = threadIdx.x; t < npx * per; t += TPB) {
+                const int px = t / per, k = t - px * per;
+                const int c = k >> 2, rr = (k >> 1) & 1, jb = k & 1;
+                dst[t] = tile_lds[(rr * g.jw + 2 * px + jb) * C1 + phi[c]];
+            }
+        }
+        __syncthreads();
     }
 }
 
-// Inverse of k_factor_out: rebuild the level's state (in the layout it had after its
-// last coupling) from the z chunk and the already decoded next level.
-__global__ void k_unfactor(int32_t* __restrict__ S, int B, int h, int w, int C, const int32_t* __restrict__ phi,
-                           int c_keep, const int32_t* __restrict__ z, long long d, long long zoff,
-                           const int32_t* __restrict__ Snext) {
-    const long long n = (long long)B * C * h * w;
-    for (long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x; t < n; t += (long long)gridDim.x * blockDim.x) {
-        const int j = (int)(t % w);
-        const int i = (int)((t / w) % h);
-        const int c = (int)((t / ((long long)w * h)) % C);
-        const int b = (int)(t / ((long long)w * h * C));
-        int v;
-        if (c >= c_keep) {
-            v = z[(long long)b * d + zoff + ((long long)(c - c_keep) * h + i) * w + j];
-        } else {
-            const int h2 = h / 2, w2 = w / 2;
-            v = Snext[(((long long)b * h2 + i / 2) * w2 + j / 2) * (4 * c_keep) + 4 * c + 2 * (i & 1) + (j & 1)];
+// Inverse of k_factor_out: rebuild the level's state (in the layout it had after its last coupling) from
+// the z chunk and the already decoded next level; same tiles, the other way round.
+__global__ __launch_bounds__(TPB) void k_unfactor(int32_t* __restrict__ S, const SplitGeom g,
+                                                  const int32_t* __restrict__ phi, const int32_t* __restrict__ z,
+                                                  const int32_t* __restrict__ Snext) {
+    extern __shared__ int32_t tile_lds[];
+    const int C = g.C, C1 = C + 1;
+    const long long ntiles = (long long)g.B * g.tiles_i * g.tiles_j;
+    for (long long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        int b, i0, j0, rows, cols;
+        split_tile(g, tile, b, i0, j0, rows, cols);
+        const int ce = C - g.c_keep;
+        for (int t = threadIdx.x; t < ce * rows * cols; t += TPB) {
+            const int jj = t % cols, q = t / cols;
+            const int rr = q % rows, c = q / rows;
+            tile_lds[(rr * g.jw + jj) * C1 + phi[g.c_keep + c]] =
+                z[(long long)b * g.d + g.zoff + ((long long)c * g.h + i0 + rr) * g.w + j0 + jj];
         }
-        S[(((long long)b * h + i) * w + j) * C + phi[c]] = v;
+        if (g.c_keep > 0) {
+            const int per = 4 * g.c_keep, npx = cols / 2;
+            const int32_t* src = Snext + (((long long)b * (g.h / 2) + i0 / 2) * (g.w / 2) + j0 / 2) * per;
+            for (int t = threadIdx.x; t < npx * per; t += TPB) {
+                const int px = t / per, k = t - px * per;
+                const int c = k >> 2, rr = (k >> 1) & 1, jb = k & 1;
+                tile_lds[(rr * g.jw + 2 * px + jb) * C1 + phi[c]] = src[t];
+            }
+        }
+        __syncthreads();
+        const int run = cols * C;
+        for (int t = threadIdx.x; t < rows * run; t += TPB) {
+            const int rr = t / run, rem = t - rr * run;
+            const int jj = rem / C, pc = rem - jj * C;
+            S[(((long long)b * g.h + i0 + rr) * g.w + j0) * C + rem] = tile_lds[(rr * g.jw + jj) * C1 + pc];
+        }
+        __syncthreads();
     }
 }
 
@@ -194,19 +252,43 @@ hipError_t launch_quant_in(const int32_t* S, int npix, int h, int w, int C, cons
     return hipGetLastError();
 }
 
+// Tile geometry of the split passes: two rows x jw columns, jw even and as wide as 32 KB of LDS allow.
+static bool split_geom(int B, int h, int w, int C, int c_keep, long long d, long long zoff, SplitGeom& g, size_t& lds) {
+    if (B <= 0 || h < 1 || w < 1 || C < 1 || c_keep < 0 || c_keep > C) return false;
+    if (c_keep > 0 && ((h | w) & 1)) return false;  // a level that is squeezed further has even sides
+    int jw = (32 * 1024 / 4) / (2 * (C + 1));
+    jw &= ~1;
+    if (jw < 2) return false;
+    if (jw > w) jw = w;  // (an odd w only occurs at the last level, where nothing is paired)
+    g.B = B; g.h = h; g.w = w; g.C = C; g.c_keep = c_keep; g.jw = jw;
+    g.tiles_j = (w + jw - 1) / jw;
+    g.tiles_i = (h + 1) / 2;
+    g.d = d; g.zoff = zoff;
+    lds = (size_t)2 * jw * (C + 1) * 4;
+    return true;
+}
+
 hipError_t launch_factor_out(const int32_t* S, int B, int h, int w, int C, const int32_t* phi, int c_keep, int32_t* z,
                              long long d, long long zoff, int32_t* Snext, hipStream_t st) {
     if (B <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_factor_out, dim3(grid_for((long long)B * C * h * w)), dim3(TPB), 0, st, S, B, h, w, C, phi,
-                       c_keep, z, d, zoff, Snext);
+    SplitGeom g;
+    size_t lds = 0;
+    if (!split_geom(B, h, w, C, c_keep, d, zoff, g, lds) || (c_keep > 0 && !Snext)) return hipErrorInvalidValue;
+    const long long ntiles = (long long)B * g.tiles_i * g.tiles_j;
+    hipLaunchKernelGGL(k_factor_out, dim3((unsigned)(ntiles > 256 * 16 ? 256 * 16 : ntiles)), dim3(TPB), lds, st, S, g, phi, z,
+                       Snext);
     return hipGetLastError();
 }
 
 hipError_t launch_unfactor(int32_t* S, int B, int h, int w, int C, const int32_t* phi, int c_keep, const int32_t* z,
                            long long d, long long zoff, const int32_t* Snext, hipStream_t st) {
     if (B <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_unfactor, dim3(grid_for((long long)B * C * h * w)), dim3(TPB), 0, st, S, B, h, w, C, phi,
-                       c_keep, z, d, zoff, Snext);
+    SplitGeom g;
+    size_t lds = 0;
+    if (!split_geom(B, h, w, C, c_keep, d, zoff, g, lds) || (c_keep > 0 && !Snext)) return hipErrorInvalidValue;
+    const long long ntiles = (long long)B * g.tiles_i * g.tiles_j;
+    hipLaunchKernelGGL(k_unfactor, dim3((unsigned)(ntiles > 256 * 16 ? 256 * 16 : ntiles)), dim3(TPB), lds, st, S, g, phi, z,
+                       Snext);
     return hipGetLastError();
 }
 
