@@ -77,7 +77,7 @@ def _spread(batch, n, seed):
     return tuple(sorted(fixed + rest[:max(0, n - len(fixed))]))
 
 
-@pytest.mark.timeout(600)
+@pytest.mark.timeout(900)
 def test_cfg3_sampled(capsys):
     _sampled(capsys, "cfg3", CONFIGS["cfg3"].batch, sample=_spread(256, 32, 3), invariance=(7,), chunk=53)
 

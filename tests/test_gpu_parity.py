@@ -325,3 +325,26 @@ def test_epilogue_at_the_saturation_edges(relu, edge, b, side, c_in):
         assert -128 in seen and -127 in seen
     else:
         assert 0 in seen
+
+
+@pytest.mark.parametrize("c_in,k,b,side,tiles", [(64, 3, 2, 16, 32), (256, 1, 136, 32, 544)])
+def test_conv_probe_timeline(c_in, k, b, side, tiles):
+    """The per-tile timeline is measurement support: it must not change the layer's result, report one
+    row per output tile that ran, and its stamps must be ordered (start <= first operands <= k loop done
+    <= epilogue done) with a plausible shader clock. Small case: plain kernel (64x64 tiles); large case: the
+    persistent kernel (256x256 tiles, 544 of them on one workgroup per CU)."""
+    c_out = 256
+    rng = np.random.default_rng(5 + c_in)
+    x = np.maximum(rng.integers(-128, 128, (b, c_in, side, side)), 0).astype(np.int8)
+    W = rng.integers(-127, 128, (c_out, c_in, k, k)).astype(np.int8)
+    bias = rng.integers(-3000, 3000, c_out).astype(np.int32)
+    M = rng.integers(1 << 30, (1 << 31) - 1, c_out).astype(np.int32)
+    shift = rng.integers(38, 42, c_out).astype(np.uint8)
+    y0, _ = iodf.iodf_conv_probe(x, W, bias, M, shift, relu=True, iters=1)
+    y1, us, tl = iodf.iodf_conv_probe_timeline(x, W, bias, M, shift, relu=True, iters=2)
+    assert np.array_equal(y0, y1) and us > 0
+    assert tl.shape == (tiles, 8)
+    assert (tl[:, 0] <= tl[:, 1]).all() and (tl[:, 1] <= tl[:, 2]).all() and (tl[:, 2] <= tl[:, 3]).all()
+    wall = (tl[:, 3] - tl[:, 0]).astype(np.float64)          # 10 ns ticks
+    ghz = (tl[:, 5] - tl[:, 4]) / np.maximum(wall, 1) * 0.1
+    assert (wall > 0).all() and 0.3 < np.median(ghz) < 3.0
