@@ -706,6 +706,252 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
     trace_stamp(a, bid, 3, tid);
 }
 
+// Hand-placed LDS fragment reads (see conv_igemm_ks2). The destination is an output of the read statement
+// and an in/out operand of the wait that covers it, so no use of it can be scheduled ahead of that wait.
+template <int OFF>
+__device__ __forceinline__ void lds_read_b128(v4i& d, const unsigned addr) {
+    static_assert(OFF >= 0 && OFF < 65536, "16-bit offset field");
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFF));
+}
+// at most VM vector-memory operations and LG LDS operations of this wave outstanding, then the barrier
+template <int VM, int LG>
+__device__ __forceinline__ void wait_frags_then_barrier(v4i& w, v4i& x) {
+    static_assert(VM >= 0 && VM < 64 && LG >= 0 && LG < 16, "counter widths");
+    asm volatile("s_waitcnt vmcnt(%2) lgkmcnt(%3)\n\ts_barrier" : "+v"(w), "+v"(x) : "n"(VM), "n"(LG) : "memory");
+}
+__device__ __forceinline__ void wait_all_frags(v4i (&w)[3], v4i (&x)[3]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(x[0]), "+v"(x[1]), "+v"(x[2]) : : "memory");
+}
+
+// Small tiles on twice the waves. A 64x64 tile gives each of four waves one MFMA per 32-deep k-step: such
+// a wave runs at the pace of its own instruction stream (loads and their addresses, fragment reads, waits:
+// some 25 instructions per k-tile around 64 cycles of matrix work), and with one wave per SIMD nothing
+// fills the gaps. Here 2 x WC x WP waves share the tile: group kh = 0 multiplies the first 32-deep k-step
+// of every k-tile, group kh = 1 the second, every wave issues half the loads, and the two waves of a SIMD
+// interleave. The two groups' partial sums (integers: any order of addition gives the same result) meet
+// once, through LDS, before the epilogue, which group 0 runs. Fast epilogues and unsplit reductions only;
+// ring, swizzle and waits are those of conv_igemm's small-tile loop.
+template <int BC, int BP, int WC, int WP, int NST, int EPI>
+__global__ __launch_bounds__(WC* WP * 128) void conv_igemm_ks2(const ConvArgs a, const int npb, const int ncb) {
+    static_assert(EPI != EPI_ANY, "fast epilogues only");
+    constexpr int NQ = WC * WP, NW = 2 * NQ;
+    constexpr int WTC = BC / WC, WTP = BP / WP;
+    constexpr int TC = WTC / 32, TP = WTP / 32;
+    constexpr int WSEG = BC / 16, SEGS = (BC + BP) / 16;  // 16-row segments = wave-wide loads per k-tile
+    constexpr int LPT = SEGS / NW;                        // loads per wave per k-tile
+    constexpr int STAGE = (BC + BP) * KT;
+    constexpr int FR = TC + TP;                           // fragment reads per wave per k-tile
+    static_assert(WTC % 32 == 0 && WTP % 32 == 0, "wave tile must be a multiple of 32x32");
+    static_assert(SEGS % NW == 0 && LPT >= 1 && WSEG % LPT == 0, "a wave loads weight rows or pixel rows, not both");
+    static_assert(NST == 9 && (NST - 2) * LPT < 64, "nine stages, one per tap");
+
+    extern __shared__ __align__(1024) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wq = wave % NQ, kh = wave / NQ;
+    const int wc = wq % WC, wp = wq / WC;
+
+    const int bid = blockIdx.x;
+    const int xcd = bid & 7, slot = bid >> 3;
+    const int pb = (slot / ncb) * 8 + xcd, cb = slot % ncb;
+    if (pb >= npb) return;
+    const int p0 = pb * BP, c0 = cb * BC;
+    if (c0 >= a.n_store) return;
+    trace_stamp(a, bid, 0, tid);
+
+    const int nkt = a.taps * (a.cin_pad / KT);
+    const long long wtile = (long long)a.n_pad * KT;
+    const int hw = a.h * a.w;
+    const int W2 = a.w + 2, PP = (a.h + 2) * W2;
+
+    // This wave's LPT segments of a stage: weight rows for the first WSEG / LPT waves, pixel rows for the
+    // rest. Either way the wave follows one stream: a fixed 64-bit base in SGPRs, a 32-bit position that
+    // advances by `inc` bytes per k-tile (weights: one k-tile; pixels of a 1x1 layer: one plane) or by
+    // `inc9` after the ninth tap (pixels of a 3x3 layer: one plane), a per-tap byte offset (pixels of a 3x3
+    // layer: kernel row and column; the lane offsets already point at pixel (i-1, j-1)), and a last valid
+    // position at which it stops: past the last k-tile the same tile lands again in a stage nobody reads,
+    // which keeps the loads per step constant. The launcher checks that the positions fit 32 bits.
+    const int lrow = lane >> 2;
+    const int lpart = (lane & 3) ^ ((lane >> 4) & 3);
+    const bool loads_w = wave * LPT < WSEG;
+    unsigned loff[LPT];
+#pragma unroll
+    for (int u = 0; u < LPT; ++u) {
+        const int seg = wave * LPT + u;
+        int m = p0 + (seg - WSEG) * 16 + lrow;
+        m = m < a.npix ? (m < 0 ? 0 : m) : a.npix - 1;
+        loff[u] = loads_w ? (unsigned)(seg * 1024 + lrow * KT + lpart * 16)
+                          : (unsigned)(bordered_pos(a, m, hw, W2, PP) - (a.taps == 9 ? W2 + 1 : 0)) * KT + (unsigned)(lpart * 16);
+    }
+    const int planes = a.cin_pad / KT;
+    const int8_t* const sbase = loads_w ? a.wgt + (long long)c0 * KT : a.in + (long long)a.in_chunk0 * a.in_plane;
+    const unsigned inc = loads_w ? (unsigned)wtile : a.taps == 9 ? 0u : (unsigned)a.in_plane;
+    const unsigned inc9 = loads_w ? 0u : (unsigned)a.in_plane;
+    const unsigned pos_last = loads_w ? (unsigned)(nkt - 1) * (unsigned)wtile : (unsigned)(planes - 1) * (unsigned)a.in_plane;
+    const unsigned trow = loads_w ? 0u : (unsigned)(W2 * KT), tcol = loads_w ? 0u : (unsigned)KT;
+    unsigned pos = 0;
+
+    // two accumulators per output block, used by alternate k-tiles; group 0's first starts at the bias
+    const int half = lane >> 5, l32 = lane & 31;
+    v16i acc[TC][TP], acc1[TC][TP];
+    static_for<TC>([&](auto tc_) {
+        constexpr int tc = decltype(tc_)::value;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            v4i b4 = {0, 0, 0, 0};
+            if (kh == 0) b4 = *(const v4i*)(a.bias + c0 + wc * WTC + tc * 32 + g * 8 + half * 4);
+            static_for<TP>([&](auto tp_) {
+                constexpr int tp = decltype(tp_)::value;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    acc[tc][tp][g * 4 + e] = b4[e];
+                    acc1[tc][tp][g * 4 + e] = 0;
+                }
+            });
+        }
+    });
+    int* const cst = (int*)(lds + NST * STAGE);  // [3][BC]: clamp bound, multiplier, shift
+    int cb_v = 0, cm_v = 0, cs_v = 0;
+    if (tid < BC) {
+        cb_v = EPI == EPI_FAST_RELU ? a.clamp_hi[c0 + tid] : 0;
+        cm_v = a.mul[c0 + tid];
+        cs_v = a.shift[c0 + tid];
+    }
+
+    typedef const void __attribute__((address_space(1))) * gptr_t;
+    typedef void __attribute__((address_space(3))) * lptr_t;
+    auto issue = [&](auto stage_, auto tap_, auto taps_) {
+        constexpr int stage = decltype(stage_)::value, tap = decltype(tap_)::value, taps = decltype(taps_)::value;
+        unsigned char* sb = lds + stage * STAGE + wave * (LPT * 1024);
+        const unsigned at = taps == 9 ? pos + (tap / 3) * trow + (tap % 3) * tcol : pos;
+#pragma unroll
+        for (int u = 0; u < LPT; ++u)
+            __builtin_amdgcn_global_load_lds((gptr_t)(sbase + (at + loff[u])), (lptr_t)(sb + u * 1024), 16, 0, 0);
+        const unsigned nx = pos + (taps == 9 && tap == 8 ? inc + inc9 : inc);
+        pos = nx < pos_last ? nx : pos_last;
+    };
+    if (a.taps == 9)
+        static_for<NST - 1>([&](auto t_) { issue(t_, t_, std::integral_constant<int, 9>{}); });
+    else
+        static_for<NST - 1>([&](auto t_) { issue(t_, std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{}); });
+    if (tid < BC) {
+        cst[tid] = cb_v;
+        cst[BC + tid] = cm_v;
+        cst[2 * BC + tid] = cs_v;
+    }
+
+    // This wave's k-step of a k-tile is read two k-tiles ahead into three rotating register sets. The reads
+    // and the waits for them are written out by hand: the compiler, left to place the lgkmcnt waits itself,
+    // asks for lgkmcnt(0) before an MFMA with younger reads in flight, which puts one LDS latency into every
+    // step (a step then takes at least that latency plus the barrier). Written this way a fragment register
+    // is an output of its ds_read statement and an in/out operand of the wait that covers it, so no use can
+    // move ahead of that wait; only the reads of the newest k-tile are pending at a barrier.
+    static_assert(TC == 1 && TP == 1, "operand lists below are written for one MFMA per wave and k-step");
+    const int sw = (l32 >> 2) & 3;
+    const int off = ((half ^ sw) * 16) ^ (kh * 32);
+    const unsigned ldsa = (unsigned)(unsigned long long)(lptr_t)lds;
+    const unsigned wl0 = ldsa + (wc * WTC + l32) * KT + off, al0 = ldsa + BC * KT + (wp * WTP + l32) * KT + off;
+    const unsigned wl8 = wl0 + 8 * STAGE, al8 = al0 + 8 * STAGE;  // a ds_read offset has 16 bits: stage 8 gets its own base
+    v4i fw[3], fa[3];
+    auto read_tile = [&](auto stage_, auto set_) {
+        constexpr int stage = decltype(stage_)::value, set = decltype(set_)::value;
+        if constexpr (stage < 8) {
+            lds_read_b128<stage * STAGE>(fw[set], wl0);
+            lds_read_b128<stage * STAGE>(fa[set], al0);
+        } else {
+            lds_read_b128<0>(fw[set], wl8);
+            lds_read_b128<0>(fa[set], al8);
+        }
+    };
+    // at most VM tile loads and LG fragment reads of this wave outstanding, then the barrier; set `set_` is
+    // what the MFMAs after it use
+    auto wait_then_barrier = [&](auto vm_, auto lg_, auto set_) {
+        constexpr int set = decltype(set_)::value;
+        wait_frags_then_barrier<decltype(vm_)::value, decltype(lg_)::value>(fw[set], fa[set]);
+    };
+    auto mma_tile = [&](auto set_, auto which_) {
+        constexpr int set = decltype(set_)::value, which = decltype(which_)::value;
+        if constexpr (which == 0)
+            acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[set], fa[set], acc[0][0], 0, 0, 0);
+        else
+            acc1[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[set], fa[set], acc1[0][0], 0, 0, 0);
+    };
+    wait_tiles_then_barrier<(NST - 2) * LPT>();  // tile 0 has landed
+    trace_stamp(a, bid, 1, tid);
+    auto loop = [&](auto taps_) {
+        constexpr int taps = decltype(taps_)::value;
+        using I0 = std::integral_constant<int, 0>;
+        using I1 = std::integral_constant<int, 1>;
+        read_tile(I0{}, I0{});
+        // tile 1 has landed (a repeat of tile 0 when there is only one), set 0 has arrived
+        wait_then_barrier(std::integral_constant<int, (NST - 3) * LPT>{}, I0{}, I0{});
+        read_tile(I1{}, I1{});
+        for (int kt = 0; kt < nkt; kt += NST) {
+            const int left = nkt - kt;
+            static_for<NST>([&](auto i_) {
+                constexpr int i = decltype(i_)::value;
+                // (a 3x3 layer has whole rounds of nine k-tiles)
+                if (taps == 9 || left > i) {
+                    // tile kt+i+NST-1 goes into the stage of tile kt+i-1; its tap is (i + 8) mod 9
+                    issue(std::integral_constant<int, (i + NST - 1) % NST>{},
+                          std::integral_constant<int, taps == 9 ? (i + 8) % 9 : 0>{}, taps_);
+                    // tile kt+i+2 has landed; of this wave's fragment reads only those of tile kt+i+1 may be pending
+                    wait_then_barrier(std::integral_constant<int, (NST - 3) * LPT>{}, std::integral_constant<int, FR>{},
+                                      std::integral_constant<int, i % 3>{});
+                    read_tile(std::integral_constant<int, (i + 2) % NST>{}, std::integral_constant<int, (i + 2) % 3>{});
+                    mma_tile(std::integral_constant<int, i % 3>{}, std::integral_constant<int, i % 2>{});
+                }
+            });
+        }
+        // fragment reads past the last k-tile are still on their way to registers the compiler takes for free
+        wait_all_frags(fw, fa);
+    };
+    if (a.taps == 9) loop(std::integral_constant<int, 9>{});
+    else loop(std::integral_constant<int, 1>{});
+    trace_stamp(a, bid, 2, tid);
+
+    // group 1 hands its sums to group 0 through LDS (an area of its own: loads issued past the last
+    // k-tile may still be landing in the ring): 16 bytes per lane and register quad, lane-contiguous
+    unsigned char* const red = lds + NST * STAGE + 1024 + wq * (TC * TP * 4096) + lane * 16;
+    if (kh == 1) {
+        static_for<TC>([&](auto tc_) {
+            constexpr int tc = decltype(tc_)::value;
+            static_for<TP>([&](auto tp_) {
+                constexpr int tp = decltype(tp_)::value;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    v4i q;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) q[e] = acc[tc][tp][g * 4 + e] + acc1[tc][tp][g * 4 + e];
+                    *(v4i*)(red + ((tc * TP + tp) * 4 + g) * 1024) = q;
+                }
+            });
+        });
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if (kh == 0) {
+        static_for<TC>([&](auto tc_) {
+            constexpr int tc = decltype(tc_)::value;
+            static_for<TP>([&](auto tp_) {
+                constexpr int tp = decltype(tp_)::value;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const v4i q = *(const v4i*)(red + ((tc * TP + tp) * 4 + g) * 1024);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[tc][tp][g * 4 + e] += acc1[tc][tp][g * 4 + e] + q[e];
+                }
+            });
+        });
+        if constexpr (EPI == EPI_FAST_RELU)
+            conv_epilogue_fast<TC, TP, true>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw, cst, BC, wc * WTC);
+        else
+            conv_epilogue_fast<TC, TP, false>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw, cst, BC, wc * WTC);
+    }
+    // the loads issued past the last k-tile must have landed before the wave retires and its LDS is reused
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    trace_stamp(a, bid, 3, tid);
+}
+
 // Persistent form of conv_igemm for launches with several output tiles per CU (fast epilogues only,
 // no split-K, a k-tile count that is a multiple of NST x taps). One workgroup per CU walks the tiles
 // blockIdx.x, blockIdx.x + gridDim.x, ... The stream of k-tiles runs on across output tiles: once
@@ -991,9 +1237,15 @@ const TileCfg kTiles[] = {
     // workgroups share a CU (see conv_pick_tile)
     IODF_TILE(256, 128, 2, 2, 3),
     IODF_TILE(128, 256, 2, 2, 3),
+    // the 64x64 tile on eight waves, the k-steps of a k-tile split between two groups of four (fast
+    // epilogues only; see conv_igemm_ks2)
+    TileCfg{64, 64, (size_t)9 * (64 + 64) * KT + 1024 + 4 * 4096,
+            {nullptr, conv_igemm_ks2<64, 64, 2, 2, 9, EPI_FAST>, conv_igemm_ks2<64, 64, 2, 2, 9, EPI_FAST_RELU>},
+            512, "conv_igemm_ks2<64,64,2,2,9>"},
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 constexpr int kPair256 = 5, kPair128 = 6;  // the two-workgroups-per-CU halves of tiles 0 and 1
+constexpr int kSmall = 4, kSmallKs2 = 7;   // the 64x64 tile and its eight-wave form
 
 // Persistent form of tile 0 (see conv_igemm_persist), by fast epilogue, and its LDS bytes.
 void (*const kPersist[3])(const ConvArgs, int, int) = {nullptr, conv_igemm_persist<256, 256, 2, 4, 4, EPI_FAST>,
@@ -1024,6 +1276,7 @@ bool args_ok(const ConvArgs& a) {
 hipError_t conv_setup() {
     for (int i = 0; i < kNumTiles; ++i) {
         for (int v = 0; v < 3; ++v) {
+            if (!kTiles[i].kern[v]) continue;
             hipError_t e = hipFuncSetAttribute((const void*)kTiles[i].kern[v],
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kTiles[i].lds);
             if (e != hipSuccess) return e;
@@ -1077,7 +1330,7 @@ bool persist_ok(const ConvArgs& a, long long tiles) {
 // First tile in table order that still fills the chip (its two-per-CU half when the reduction is
 // short); otherwise the valid tile with most workgroups, and among equals the one that multiplies
 // the least padding.
-int conv_pick_tile(const ConvArgs& a) {
+static int pick_tile_by_shape(const ConvArgs& a) {
     if (!args_ok(a)) return -1;
     int best = -1;
     long long best_blocks = -1, best_work = 0;
@@ -1105,6 +1358,15 @@ int conv_pick_tile(const ConvArgs& a) {
         }
     }
     return best;
+}
+
+int conv_pick_tile(const ConvArgs& a) {
+    const int t = pick_tile_by_shape(a);
+    // hidden layers on the 64x64 tile take its eight-wave form
+    // (its load streams keep 32-bit positions)
+    const long long nkt = (long long)a.taps * (a.cin_pad / KT);
+    const bool fits = nkt * a.n_pad * KT < (1LL << 32) && (long long)(a.cin_pad / KT) * a.in_plane < (1LL << 32);
+    return t == kSmall && pick_epi(a) != EPI_ANY && fits ? kSmallKs2 : t;
 }
 
 // K splits for a layer whose tiles alone cannot fill the chip (only the general epilogue
