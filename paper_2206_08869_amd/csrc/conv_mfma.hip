@@ -706,44 +706,73 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
     trace_stamp(a, bid, 3, tid);
 }
 
-// Hand-placed LDS fragment reads (see conv_igemm_ks2). The destination is an output of the read statement
+// Hand-placed LDS fragment reads (see conv_igemm_lean). The destination is an output of the read statement
 // and an in/out operand of the wait that covers it, so no use of it can be scheduled ahead of that wait.
 template <int OFF>
 __device__ __forceinline__ void lds_read_b128(v4i& d, const unsigned addr) {
     static_assert(OFF >= 0 && OFF < 65536, "16-bit offset field");
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFF));
 }
-// at most VM vector-memory operations and LG LDS operations of this wave outstanding, then the barrier
-template <int VM, int LG>
-__device__ __forceinline__ void wait_frags_then_barrier(v4i& w, v4i& x) {
-    static_assert(VM >= 0 && VM < 64 && LG >= 0 && LG < 16, "counter widths");
-    asm volatile("s_waitcnt vmcnt(%2) lgkmcnt(%3)\n\ts_barrier" : "+v"(w), "+v"(x) : "n"(VM), "n"(LG) : "memory");
+// Marks the fragments as produced here: what uses them stays behind every asm statement before this point.
+template <int NWF, int NAF>
+__device__ __forceinline__ void tie_frags(v4i (&w)[NWF], v4i (&x)[NAF]) {
+#pragma unroll
+    for (int i = 0; i < NWF; ++i) asm volatile("" : "+v"(w[i]));
+#pragma unroll
+    for (int i = 0; i < NAF; ++i) asm volatile("" : "+v"(x[i]));
 }
-__device__ __forceinline__ void wait_all_frags(v4i (&w)[3], v4i (&x)[3]) {
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(x[0]), "+v"(x[1]), "+v"(x[2]) : : "memory");
+// at most LG LDS operations of this wave outstanding; the fragments w, x are among the completed ones
+template <int LG, int NWF, int NAF>
+__device__ __forceinline__ void wait_frags(v4i (&w)[NWF], v4i (&x)[NAF]) {
+    static_assert(LG >= 0 && LG < 16, "counter width");
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(LG) : "memory");
+    tie_frags(w, x);
+}
+// at most VM vector-memory operations and LG LDS operations of this wave outstanding, then the barrier
+template <int VM, int LG, int NWF, int NAF>
+__device__ __forceinline__ void wait_frags_then_barrier(v4i (&w)[NWF], v4i (&x)[NAF]) {
+    static_assert(VM >= 0 && VM < 64 && LG >= 0 && LG < 16, "counter widths");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(%1)\n\ts_barrier" ::"n"(VM), "n"(LG) : "memory");
+    tie_frags(w, x);
 }
 
-// Small tiles on twice the waves. A 64x64 tile gives each of four waves one MFMA per 32-deep k-step: such
-// a wave runs at the pace of its own instruction stream (loads and their addresses, fragment reads, waits:
-// some 25 instructions per k-tile around 64 cycles of matrix work), and with one wave per SIMD nothing
-// fills the gaps. Here 2 x WC x WP waves share the tile: group kh = 0 multiplies the first 32-deep k-step
-// of every k-tile, group kh = 1 the second, every wave issues half the loads, and the two waves of a SIMD
-// interleave. The two groups' partial sums (integers: any order of addition gives the same result) meet
-// once, through LDS, before the epilogue, which group 0 runs. Fast epilogues and unsplit reductions only;
-// ring, swizzle and waits are those of conv_igemm's small-tile loop.
-template <int BC, int BP, int WC, int WP, int NST, int EPI>
-__global__ __launch_bounds__(WC* WP * 128) void conv_igemm_ks2(const ConvArgs a, const int npb, const int ncb) {
+// Small and medium tiles, for launches with few pixels (the deep levels of a flow, everything at batch 1).
+// With one or two MFMAs per wave and k-step the k loop runs at the pace of a wave's instruction stream and
+// of the waits in it, not of the matrix pipe, so this kernel spends as few instructions per k-tile as it
+// can and never waits for more than it needs:
+//  - nine ring stages (= taps: stage and tap of every load are constants of nine unrolled steps, and a 3x3
+//    layer has whole rounds); a wave loads weight rows or pixel rows, not both, and follows its stream with
+//    a fixed 64-bit base in SGPRs and a 32-bit position (see below), which gives the address mode
+//    "scalar base + 32-bit lane offset": one vector add per load;
+//  - the fragments of a k-tile are read two k-tiles ahead into three rotating register sets, by hand-placed
+//    ds_reads; only the reads of the newest k-tile may be pending at a barrier, and the wait names the set
+//    the following MFMAs use (the compiler, left to itself, puts lgkmcnt(0) before the first use of a
+//    fragment, which waits for the reads just issued as well and leaves one LDS latency in every step);
+//  - two accumulators per output block take alternate k-steps, so no MFMA waits for the one before it.
+// KS = 2 puts twice the waves on the tile: a 64x64 tile gives four waves one MFMA per k-step each, and with
+// one wave per SIMD nothing fills the gaps in its stream. Group kh = 0 then multiplies the first 32-deep
+// k-step of every k-tile, group kh = 1 the second, every wave issues half the loads, and the two groups'
+// partial sums (integers: any order of addition gives the same result) meet once, through LDS, before the
+// epilogue, which group 0 runs. Fast epilogues and unsplit reductions only.
+template <int BC, int BP, int WC, int WP, int KS, int EPI>
+__global__ __launch_bounds__(WC* WP* KS * 64) void conv_igemm_lean(const ConvArgs a, const int npb, const int ncb) {
     static_assert(EPI != EPI_ANY, "fast epilogues only");
-    constexpr int NQ = WC * WP, NW = 2 * NQ;
+    static_assert(KS == 1 || KS == 2, "a k-tile has two k-steps");
+    constexpr int NST = 9;
+    constexpr int NQ = WC * WP, NW = KS * NQ;
     constexpr int WTC = BC / WC, WTP = BP / WP;
     constexpr int TC = WTC / 32, TP = WTP / 32;
+    constexpr int KSTEPS = 2 / KS;                        // k-steps of a k-tile that a wave multiplies
     constexpr int WSEG = BC / 16, SEGS = (BC + BP) / 16;  // 16-row segments = wave-wide loads per k-tile
     constexpr int LPT = SEGS / NW;                        // loads per wave per k-tile
     constexpr int STAGE = (BC + BP) * KT;
-    constexpr int FR = TC + TP;                           // fragment reads per wave per k-tile
+    constexpr int FR = KSTEPS * (TC + TP);                // fragment reads per wave per k-tile
+    constexpr int CST = 2048;                             // bytes set aside for the per-channel constants
+    constexpr int G = 65536 / STAGE, NB = (NST + G - 1) / G;  // a ds_read offset has 16 bits: G stages per base address
     static_assert(WTC % 32 == 0 && WTP % 32 == 0, "wave tile must be a multiple of 32x32");
     static_assert(SEGS % NW == 0 && LPT >= 1 && WSEG % LPT == 0, "a wave loads weight rows or pixel rows, not both");
-    static_assert(NST == 9 && (NST - 2) * LPT < 64, "nine stages, one per tap");
+    static_assert((NST - 2) * LPT < 64 && FR < 16, "counter widths");
+    static_assert(3 * BC * (int)sizeof(int) <= CST && BC <= NW * 64 && G >= 1, "constants");
 
     extern __shared__ __align__(1024) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -791,7 +820,7 @@ __global__ __launch_bounds__(WC* WP * 128) void conv_igemm_ks2(const ConvArgs a,
     const unsigned trow = loads_w ? 0u : (unsigned)(W2 * KT), tcol = loads_w ? 0u : (unsigned)KT;
     unsigned pos = 0;
 
-    // two accumulators per output block, used by alternate k-tiles; group 0's first starts at the bias
+    // two accumulators per output block; the first one of group 0 starts at the bias
     const int half = lane >> 5, l32 = lane & 31;
     v16i acc[TC][TP], acc1[TC][TP];
     static_for<TC>([&](auto tc_) {
@@ -840,41 +869,52 @@ __global__ __launch_bounds__(WC* WP * 128) void conv_igemm_ks2(const ConvArgs a,
         cst[2 * BC + tid] = cs_v;
     }
 
-    // This wave's k-step of a k-tile is read two k-tiles ahead into three rotating register sets. The reads
-    // and the waits for them are written out by hand: the compiler, left to place the lgkmcnt waits itself,
-    // asks for lgkmcnt(0) before an MFMA with younger reads in flight, which puts one LDS latency into every
-    // step (a step then takes at least that latency plus the barrier). Written this way a fragment register
-    // is an output of its ds_read statement and an in/out operand of the wait that covers it, so no use can
-    // move ahead of that wait; only the reads of the newest k-tile are pending at a barrier.
-    static_assert(TC == 1 && TP == 1, "operand lists below are written for one MFMA per wave and k-step");
+    // fragment addresses: row l32 of each 32-row block, k-part (2 * k-step + half), swizzled as the loads put it
     const int sw = (l32 >> 2) & 3;
-    const int off = ((half ^ sw) * 16) ^ (kh * 32);
+    const int off0 = (half ^ sw) * 16;
     const unsigned ldsa = (unsigned)(unsigned long long)(lptr_t)lds;
-    const unsigned wl0 = ldsa + (wc * WTC + l32) * KT + off, al0 = ldsa + BC * KT + (wp * WTP + l32) * KT + off;
-    const unsigned wl8 = wl0 + 8 * STAGE, al8 = al0 + 8 * STAGE;  // a ds_read offset has 16 bits: stage 8 gets its own base
-    v4i fw[3], fa[3];
+    unsigned wadr[KSTEPS][NB], aadr[KSTEPS][NB];
+#pragma unroll
+    for (int j = 0; j < KSTEPS; ++j)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int ks = KS == 2 ? kh : j;
+            wadr[j][b] = ldsa + b * G * STAGE + (wc * WTC + l32) * KT + (off0 ^ (ks * 32));
+            aadr[j][b] = ldsa + b * G * STAGE + BC * KT + (wp * WTP + l32) * KT + (off0 ^ (ks * 32));
+        }
+    v4i fw[3][KSTEPS * TC], fa[3][KSTEPS * TP];
     auto read_tile = [&](auto stage_, auto set_) {
         constexpr int stage = decltype(stage_)::value, set = decltype(set_)::value;
-        if constexpr (stage < 8) {
-            lds_read_b128<stage * STAGE>(fw[set], wl0);
-            lds_read_b128<stage * STAGE>(fa[set], al0);
-        } else {
-            lds_read_b128<0>(fw[set], wl8);
-            lds_read_b128<0>(fa[set], al8);
-        }
+        static_for<KSTEPS>([&](auto j_) {
+            constexpr int j = decltype(j_)::value;
+            static_for<TC>([&](auto tc_) {
+                constexpr int tc = decltype(tc_)::value;
+                lds_read_b128<(stage % G) * STAGE + tc * 32 * KT>(fw[set][j * TC + tc], wadr[j][stage / G]);
+            });
+            static_for<TP>([&](auto tp_) {
+                constexpr int tp = decltype(tp_)::value;
+                lds_read_b128<(stage % G) * STAGE + tp * 32 * KT>(fa[set][j * TP + tp], aadr[j][stage / G]);
+            });
+        });
     };
-    // at most VM tile loads and LG fragment reads of this wave outstanding, then the barrier; set `set_` is
-    // what the MFMAs after it use
-    auto wait_then_barrier = [&](auto vm_, auto lg_, auto set_) {
-        constexpr int set = decltype(set_)::value;
-        wait_frags_then_barrier<decltype(vm_)::value, decltype(lg_)::value>(fw[set], fa[set]);
-    };
-    auto mma_tile = [&](auto set_, auto which_) {
-        constexpr int set = decltype(set_)::value, which = decltype(which_)::value;
-        if constexpr (which == 0)
-            acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[set], fa[set], acc[0][0], 0, 0, 0);
-        else
-            acc1[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[set], fa[set], acc1[0][0], 0, 0, 0);
+    // k-tile number i of a round: with one group, k-step 0 adds into acc and k-step 1 into acc1; with two
+    // groups a wave has one k-step per k-tile and alternates by k-tile
+    auto mma_tile = [&](auto set_, auto i_) {
+        constexpr int set = decltype(set_)::value, i = decltype(i_)::value;
+        static_for<KSTEPS>([&](auto j_) {
+            constexpr int j = decltype(j_)::value;
+            constexpr int which = KS == 1 ? j : i % 2;
+            static_for<TC>([&](auto tc_) {
+                constexpr int tc = decltype(tc_)::value;
+                static_for<TP>([&](auto tp_) {
+                    constexpr int tp = decltype(tp_)::value;
+                    if constexpr (which == 0)
+                        acc[tc][tp] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[set][j * TC + tc], fa[set][j * TP + tp], acc[tc][tp], 0, 0, 0);
+                    else
+                        acc1[tc][tp] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[set][j * TC + tc], fa[set][j * TP + tp], acc1[tc][tp], 0, 0, 0);
+                });
+            });
+        });
     };
     wait_tiles_then_barrier<(NST - 2) * LPT>();  // tile 0 has landed
     trace_stamp(a, bid, 1, tid);
@@ -884,7 +924,8 @@ __global__ __launch_bounds__(WC* WP * 128) void conv_igemm_ks2(const ConvArgs a,
         using I1 = std::integral_constant<int, 1>;
         read_tile(I0{}, I0{});
         // tile 1 has landed (a repeat of tile 0 when there is only one), set 0 has arrived
-        wait_then_barrier(std::integral_constant<int, (NST - 3) * LPT>{}, I0{}, I0{});
+        wait_tiles_then_barrier<(NST - 3) * LPT>();
+        tie_frags(fw[0], fa[0]);
         read_tile(I1{}, I1{});
         for (int kt = 0; kt < nkt; kt += NST) {
             const int left = nkt - kt;
@@ -896,52 +937,66 @@ __global__ __launch_bounds__(WC* WP * 128) void conv_igemm_ks2(const ConvArgs a,
                     issue(std::integral_constant<int, (i + NST - 1) % NST>{},
                           std::integral_constant<int, taps == 9 ? (i + 8) % 9 : 0>{}, taps_);
                     // tile kt+i+2 has landed; of this wave's fragment reads only those of tile kt+i+1 may be pending
-                    wait_then_barrier(std::integral_constant<int, (NST - 3) * LPT>{}, std::integral_constant<int, FR>{},
-                                      std::integral_constant<int, i % 3>{});
+                    wait_frags_then_barrier<(NST - 3) * LPT, FR>(fw[i % 3], fa[i % 3]);
                     read_tile(std::integral_constant<int, (i + 2) % NST>{}, std::integral_constant<int, (i + 2) % 3>{});
-                    mma_tile(std::integral_constant<int, i % 3>{}, std::integral_constant<int, i % 2>{});
+                    mma_tile(std::integral_constant<int, i % 3>{}, i_);
                 }
             });
         }
         // fragment reads past the last k-tile are still on their way to registers the compiler takes for free
-        wait_all_frags(fw, fa);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        tie_frags(fw[0], fa[0]);
+        tie_frags(fw[1], fa[1]);
+        tie_frags(fw[2], fa[2]);
     };
     if (a.taps == 9) loop(std::integral_constant<int, 9>{});
     else loop(std::integral_constant<int, 1>{});
     trace_stamp(a, bid, 2, tid);
 
-    // group 1 hands its sums to group 0 through LDS (an area of its own: loads issued past the last
-    // k-tile may still be landing in the ring): 16 bytes per lane and register quad, lane-contiguous
-    unsigned char* const red = lds + NST * STAGE + 1024 + wq * (TC * TP * 4096) + lane * 16;
-    if (kh == 1) {
-        static_for<TC>([&](auto tc_) {
-            constexpr int tc = decltype(tc_)::value;
-            static_for<TP>([&](auto tp_) {
-                constexpr int tp = decltype(tp_)::value;
+    static_for<TC>([&](auto tc_) {
+        constexpr int tc = decltype(tc_)::value;
+        static_for<TP>([&](auto tp_) {
+            constexpr int tp = decltype(tp_)::value;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    v4i q;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) q[e] = acc[tc][tp][g * 4 + e] + acc1[tc][tp][g * 4 + e];
-                    *(v4i*)(red + ((tc * TP + tp) * 4 + g) * 1024) = q;
-                }
-            });
+            for (int r = 0; r < 16; ++r) acc[tc][tp][r] += acc1[tc][tp][r];
         });
+    });
+    if constexpr (KS == 2) {
+        // group 1 hands its sums to group 0 through LDS (an area of its own: loads issued past the last
+        // k-tile may still be landing in the ring): 16 bytes per lane and register quad, lane-contiguous
+        unsigned char* const red = lds + NST * STAGE + CST + wq * (TC * TP * 4096) + lane * 16;
+        if (kh == 1) {
+            static_for<TC>([&](auto tc_) {
+                constexpr int tc = decltype(tc_)::value;
+                static_for<TP>([&](auto tp_) {
+                    constexpr int tp = decltype(tp_)::value;
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        v4i q;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) q[e] = acc[tc][tp][g * 4 + e];
+                        *(v4i*)(red + ((tc * TP + tp) * 4 + g) * 1024) = q;
+                    }
+                });
+            });
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        if (kh == 0) {
+            static_for<TC>([&](auto tc_) {
+                constexpr int tc = decltype(tc_)::value;
+                static_for<TP>([&](auto tp_) {
+                    constexpr int tp = decltype(tp_)::value;
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const v4i q = *(const v4i*)(red + ((tc * TP + tp) * 4 + g) * 1024);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[tc][tp][g * 4 + e] += q[e];
+                    }
+                });
+            });
+        }
     }
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     if (kh == 0) {
-        static_for<TC>([&](auto tc_) {
-            constexpr int tc = decltype(tc_)::value;
-            static_for<TP>([&](auto tp_) {
-                constexpr int tp = decltype(tp_)::value;
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const v4i q = *(const v4i*)(red + ((tc * TP + tp) * 4 + g) * 1024);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[tc][tp][g * 4 + e] += acc1[tc][tp][g * 4 + e] + q[e];
-                }
-            });
-        });
         if constexpr (EPI == EPI_FAST_RELU)
             conv_epilogue_fast<TC, TP, true>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw, cst, BC, wc * WTC);
         else
@@ -1058,14 +1113,33 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm_persist(const ConvArgs
     const int wl0 = (wc * WTC + l32) * KT, al0 = BC * KT + (wp * WTP + l32) * KT;
     v16i acc[TC][TP];
     v4i wf0[TC], af0[TP], wf1[TC], af1[TP];
-    auto read_frags = [&](int stage, int ks, v4i (&wf)[TC], v4i (&af)[TP]) {
-        const unsigned char* sb = lds + stage * STAGE;
-        const int off = off0 ^ (ks * 32);
+    // Fragment reads and the waits for them are placed by hand (lds_read_b128, wait_frags): left to the
+    // compiler, every first use of a fragment is preceded by lgkmcnt(0), which also waits for the reads of
+    // the next k-step issued just before, so both waves of a SIMD stall for an LDS latency twice per k-tile,
+    // at about the same time since the barrier keeps them in step. A ds_read offset has 16 bits and a stage
+    // 32 KB: one base address per operand, k-step and pair of stages.
+    const unsigned ldsa = (unsigned)(unsigned long long)(lptr_t)lds;
+    unsigned wadr[2][2], aadr[2][2];  // [k-step][stage pair]
 #pragma unroll
-        for (int tc = 0; tc < TC; ++tc) wf[tc] = *(const v4i*)(sb + wl0 + tc * 32 * KT + off);
+    for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-        for (int tp = 0; tp < TP; ++tp) af[tp] = *(const v4i*)(sb + al0 + tp * 32 * KT + off);
+        for (int sp = 0; sp < 2; ++sp) {
+            wadr[ks][sp] = ldsa + sp * 2 * STAGE + wl0 + (off0 ^ (ks * 32));
+            aadr[ks][sp] = ldsa + sp * 2 * STAGE + al0 + (off0 ^ (ks * 32));
+        }
+    static_assert(NST == 4 && STAGE + (TC > TP ? TC : TP) * 32 * KT <= 65536, "two stages per base address");
+    auto read_frags = [&](auto stage_, auto ks_, v4i (&wf)[TC], v4i (&af)[TP]) {
+        constexpr int stage = decltype(stage_)::value, ks = decltype(ks_)::value;
+        static_for<TC>([&](auto tc_) {
+            constexpr int tc = decltype(tc_)::value;
+            lds_read_b128<(stage & 1) * STAGE + tc * 32 * KT>(wf[tc], wadr[ks][stage >> 1]);
+        });
+        static_for<TP>([&](auto tp_) {
+            constexpr int tp = decltype(tp_)::value;
+            lds_read_b128<(stage & 1) * STAGE + tp * 32 * KT>(af[tp], aadr[ks][stage >> 1]);
+        });
     };
+    constexpr int FR = TC + TP;  // fragment reads per k-step
     auto mma = [&](v4i (&wf)[TC], v4i (&af)[TP]) {
         static_for<TC>([&](auto tc_) {
             constexpr int tc = decltype(tc_)::value;
@@ -1137,16 +1211,16 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm_persist(const ConvArgs
                     });
                 }
             });
-            read_frags(0, 0, wf0, af0);
+            using I0 = std::integral_constant<int, 0>;
+            using I1 = std::integral_constant<int, 1>;
+            read_frags(I0{}, I0{}, wf0, af0);
             for (int kt = 0; kt < nkt; kt += U) {
                 static_for<U>([&](auto i_) {
                     constexpr int i = decltype(i_)::value;
                     constexpr int st = i % NST;
-                    read_frags(st, 1, wf1, af1);
-                    // 3x3 layers: keep the fragment reads of the next k-step ahead of the MFMAs of this one (left
-                    // alone, the scheduler sinks them to just before their first use and the wave waits for the
-                    // LDS; measured 2.8 % on these layers, nothing on 1x1 layers, a loss in the plain kernel)
-                    if constexpr (taps == 9) __builtin_amdgcn_sched_barrier(0);
+                    // second k-step's fragments on their way while the first k-step multiplies
+                    read_frags(std::integral_constant<int, st>{}, I1{}, wf1, af1);
+                    wait_frags<FR>(wf0, af0);
                     mma(wf0, af0);
                     // k-tile kt + i + NST - 1 of the load stream goes into the stage of k-tile kt + i - 1;
                     // in the last round that stream reaches the end of this output tile at step U - NST + 1
@@ -1155,12 +1229,16 @@ __global__ __launch_bounds__(WC* WP * 64) void conv_igemm_persist(const ConvArgs
                     }
                     issue_static(std::integral_constant<int, (i + NST - 1) % NST>{},
                                  std::integral_constant<int, taps == 9 ? (i + NST - 1) % 9 : 0>{}, taps_);
+                    // (lgkmcnt(0): nobody still reads the stage that the next step's loads overwrite)
                     wait_tiles_then_barrier<(NST - 2) * LPT>();
-                    read_frags((st + 1) % NST, 0, wf0, af0);
-                    if constexpr (taps == 9) __builtin_amdgcn_sched_barrier(0);
+                    tie_frags(wf1, af1);
+                    read_frags(std::integral_constant<int, (st + 1) % NST>{}, I0{}, wf0, af0);
                     mma(wf1, af1);
                 });
             }
+            // the reads of the next tile's first fragments are still on their way to registers that the
+            // epilogue is free to use
+            wait_frags<0>(wf0, af0);
             const int nxt = next_slot(cur + (int)gridDim.x);
             trace_stamp(a, cur, 2, tid);
             if constexpr (EPI == EPI_FAST_RELU)
@@ -1237,15 +1315,18 @@ const TileCfg kTiles[] = {
     // workgroups share a CU (see conv_pick_tile)
     IODF_TILE(256, 128, 2, 2, 3),
     IODF_TILE(128, 256, 2, 2, 3),
-    // the 64x64 tile on eight waves, the k-steps of a k-tile split between two groups of four (fast
-    // epilogues only; see conv_igemm_ks2)
-    TileCfg{64, 64, (size_t)9 * (64 + 64) * KT + 1024 + 4 * 4096,
-            {nullptr, conv_igemm_ks2<64, 64, 2, 2, 9, EPI_FAST>, conv_igemm_ks2<64, 64, 2, 2, 9, EPI_FAST_RELU>},
-            512, "conv_igemm_ks2<64,64,2,2,9>"},
+    // lean forms of the 64x64 tile (eight waves, the k-steps split between two groups of four) and of the
+    // 128x128 tile for layers with a fast epilogue (see conv_igemm_lean)
+    TileCfg{64, 64, (size_t)9 * (64 + 64) * KT + 2048 + 4 * 4096,
+            {nullptr, conv_igemm_lean<64, 64, 2, 2, 2, EPI_FAST>, conv_igemm_lean<64, 64, 2, 2, 2, EPI_FAST_RELU>},
+            512, "conv_igemm_lean<64,64,2,2,2>"},
+    TileCfg{128, 128, (size_t)9 * (128 + 128) * KT + 2048,
+            {nullptr, conv_igemm_lean<128, 128, 4, 2, 1, EPI_FAST>, conv_igemm_lean<128, 128, 4, 2, 1, EPI_FAST_RELU>},
+            512, "conv_igemm_lean<128,128,4,2,1>"},
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 constexpr int kPair256 = 5, kPair128 = 6;  // the two-workgroups-per-CU halves of tiles 0 and 1
-constexpr int kSmall = 4, kSmallKs2 = 7;   // the 64x64 tile and its eight-wave form
+constexpr int kSmall = 4, kSmallLean = 7, kMid = 2, kMidLean = 8;  // the 64x64 and 128x128 tiles and their lean forms
 
 // Persistent form of tile 0 (see conv_igemm_persist), by fast epilogue, and its LDS bytes.
 void (*const kPersist[3])(const ConvArgs, int, int) = {nullptr, conv_igemm_persist<256, 256, 2, 4, 4, EPI_FAST>,
@@ -1362,11 +1443,12 @@ static int pick_tile_by_shape(const ConvArgs& a) {
 
 int conv_pick_tile(const ConvArgs& a) {
     const int t = pick_tile_by_shape(a);
-    // hidden layers on the 64x64 tile take its eight-wave form
+    // hidden layers on the 64x64 and 128x128 tiles take the lean kernel
     // (its load streams keep 32-bit positions)
     const long long nkt = (long long)a.taps * (a.cin_pad / KT);
     const bool fits = nkt * a.n_pad * KT < (1LL << 32) && (long long)(a.cin_pad / KT) * a.in_plane < (1LL << 32);
-    return t == kSmall && pick_epi(a) != EPI_ANY && fits ? kSmallKs2 : t;
+    if (pick_epi(a) == EPI_ANY || !fits) return t;
+    return t == kSmall ? kSmallLean : t == kMid ? kMidLean : t;
 }
 
 // K splits for a layer whose tiles alone cannot fill the chip (only the general epilogue
