@@ -256,6 +256,30 @@ def test_single_convolution_on_few_pixels_matches_oracle(c_in, c_out, k, relu, b
     _check_single_convolution(c_in, c_out, k, relu, 36, b, side, side)
 
 
+@pytest.mark.parametrize("c_in,c_out,k,relu,b,h,w,tiles", [
+    (64, 64, 1, True, 1, 4, 4, 1),          # one k-tile: every load past it repeats it
+    (640, 64, 1, True, 3, 5, 7, 2),         # ten k-tiles (one round and one step), 105 pixels: a ragged second tile
+    (64, 128, 3, False, 2, 6, 6, 4),        # nine k-tiles (one round), shortcut-free no-ReLU epilogue
+    (192, 256, 3, True, 16, 8, 8, 64),      # 27 k-tiles, 64 tiles of 64x64
+    (128, 512, 3, True, 131, 7, 9, 260),    # 128x128 tile: 65 pixel blocks (the last one ragged) x 4 channel blocks
+    (640, 512, 1, True, 128, 8, 8, 256),    # 128x128 tile, ten k-tiles
+    (64, 512, 1, False, 128, 8, 8, 256),    # 128x128 tile, one k-tile
+])
+def test_single_convolution_on_the_small_tile_kernel_matches_oracle(c_in, c_out, k, relu, b, h, w, tiles):
+    """Reduction lengths around the nine-step round of the small-tile kernel (1, 9, 10, 27 k-tiles), ragged pixel
+    tiles, both of its tile sizes; the timeline's row count (output tiles that ran = pixel blocks x channel blocks)
+    tells that the intended tiling ran."""
+    _check_single_convolution(c_in, c_out, k, relu, 36, b, h, w)
+    rng = np.random.default_rng(3)
+    x = rng.integers(0, 128, (b, c_in, h, w)).astype(np.int8)
+    W = rng.integers(-128, 128, (c_out, c_in, k, k)).astype(np.int8)
+    bias = np.zeros(c_out, np.int32)
+    M = np.full(c_out, 1 << 30, np.int32)
+    shift = np.full(c_out, 40, np.uint8)
+    _, _, tl = iodf.iodf_conv_probe_timeline(x, W, bias, M, shift, relu=relu, iters=1)
+    assert tl.shape[0] == tiles
+
+
 def _check_single_convolution(c_in, c_out, k, relu, shift_lo, b, h, w):
     import oracle
     rng = np.random.default_rng(c_in * 1000 + c_out)
