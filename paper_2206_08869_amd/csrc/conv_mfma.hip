@@ -753,10 +753,9 @@ __device__ __forceinline__ void wait_frags_then_barrier(v4i (&w)[NWF], v4i (&x)[
 // one wave per SIMD nothing fills the gaps in its stream. Group kh = 0 then multiplies the first 32-deep
 // k-step of every k-tile, group kh = 1 the second, every wave issues half the loads, and the two groups'
 // partial sums (integers: any order of addition gives the same result) meet once, through LDS, before the
-// epilogue, which group 0 runs. Fast epilogues and unsplit reductions only.
+// epilogue, which group 0 runs. Unsplit reductions only.
 template <int BC, int BP, int WC, int WP, int KS, int EPI>
 __global__ __launch_bounds__(WC* WP* KS * 64) void conv_igemm_lean(const ConvArgs a, const int npb, const int ncb) {
-    static_assert(EPI != EPI_ANY, "fast epilogues only");
     static_assert(KS == 1 || KS == 2, "a k-tile has two k-steps");
     constexpr int NST = 9;
     constexpr int NQ = WC * WP, NW = KS * NQ;
@@ -820,7 +819,8 @@ __global__ __launch_bounds__(WC* WP* KS * 64) void conv_igemm_lean(const ConvArg
     const unsigned trow = loads_w ? 0u : (unsigned)(W2 * KT), tcol = loads_w ? 0u : (unsigned)KT;
     unsigned pos = 0;
 
-    // two accumulators per output block; the first one of group 0 starts at the bias
+    // two accumulators per output block; the first one of group 0 starts at the bias (fast epilogues; the
+    // general one adds it itself and reads its constants from global memory)
     const int half = lane >> 5, l32 = lane & 31;
     v16i acc[TC][TP], acc1[TC][TP];
     static_for<TC>([&](auto tc_) {
@@ -828,7 +828,7 @@ __global__ __launch_bounds__(WC* WP* KS * 64) void conv_igemm_lean(const ConvArg
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             v4i b4 = {0, 0, 0, 0};
-            if (kh == 0) b4 = *(const v4i*)(a.bias + c0 + wc * WTC + tc * 32 + g * 8 + half * 4);
+            if (EPI != EPI_ANY && kh == 0) b4 = *(const v4i*)(a.bias + c0 + wc * WTC + tc * 32 + g * 8 + half * 4);
             static_for<TP>([&](auto tp_) {
                 constexpr int tp = decltype(tp_)::value;
 #pragma unroll
@@ -841,7 +841,7 @@ __global__ __launch_bounds__(WC* WP* KS * 64) void conv_igemm_lean(const ConvArg
     });
     int* const cst = (int*)(lds + NST * STAGE);  // [3][BC]: clamp bound, multiplier, shift
     int cb_v = 0, cm_v = 0, cs_v = 0;
-    if (tid < BC) {
+    if (EPI != EPI_ANY && tid < BC) {
         cb_v = EPI == EPI_FAST_RELU ? a.clamp_hi[c0 + tid] : 0;
         cm_v = a.mul[c0 + tid];
         cs_v = a.shift[c0 + tid];
@@ -863,7 +863,7 @@ __global__ __launch_bounds__(WC* WP* KS * 64) void conv_igemm_lean(const ConvArg
         static_for<NST - 1>([&](auto t_) { issue(t_, t_, std::integral_constant<int, 9>{}); });
     else
         static_for<NST - 1>([&](auto t_) { issue(t_, std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{}); });
-    if (tid < BC) {
+    if (EPI != EPI_ANY && tid < BC) {
         cst[tid] = cb_v;
         cst[BC + tid] = cm_v;
         cst[2 * BC + tid] = cs_v;
@@ -999,8 +999,10 @@ __global__ __launch_bounds__(WC* WP* KS * 64) void conv_igemm_lean(const ConvArg
     if (kh == 0) {
         if constexpr (EPI == EPI_FAST_RELU)
             conv_epilogue_fast<TC, TP, true>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw, cst, BC, wc * WTC);
-        else
+        else if constexpr (EPI == EPI_FAST)
             conv_epilogue_fast<TC, TP, false>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw, cst, BC, wc * WTC);
+        else
+            conv_epilogue<TC, TP>(a, acc, p0 + wp * WTP, c0 + wc * WTC, lane, hw);
     }
     // the loads issued past the last k-tile must have landed before the wave retires and its LDS is reused
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -1316,12 +1318,12 @@ const TileCfg kTiles[] = {
     IODF_TILE(256, 128, 2, 2, 3),
     IODF_TILE(128, 256, 2, 2, 3),
     // lean forms of the 64x64 tile (eight waves, the k-steps split between two groups of four) and of the
-    // 128x128 tile for layers with a fast epilogue (see conv_igemm_lean)
+    // 128x128 tile for layers whose reduction is not split (see conv_igemm_lean)
     TileCfg{64, 64, (size_t)9 * (64 + 64) * KT + 2048 + 4 * 4096,
-            {nullptr, conv_igemm_lean<64, 64, 2, 2, 2, EPI_FAST>, conv_igemm_lean<64, 64, 2, 2, 2, EPI_FAST_RELU>},
+            {conv_igemm_lean<64, 64, 2, 2, 2, EPI_ANY>, conv_igemm_lean<64, 64, 2, 2, 2, EPI_FAST>, conv_igemm_lean<64, 64, 2, 2, 2, EPI_FAST_RELU>},
             512, "conv_igemm_lean<64,64,2,2,2>"},
     TileCfg{128, 128, (size_t)9 * (128 + 128) * KT + 2048,
-            {nullptr, conv_igemm_lean<128, 128, 4, 2, 1, EPI_FAST>, conv_igemm_lean<128, 128, 4, 2, 1, EPI_FAST_RELU>},
+            {conv_igemm_lean<128, 128, 4, 2, 1, EPI_ANY>, conv_igemm_lean<128, 128, 4, 2, 1, EPI_FAST>, conv_igemm_lean<128, 128, 4, 2, 1, EPI_FAST_RELU>},
             512, "conv_igemm_lean<128,128,4,2,1>"},
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
@@ -1443,12 +1445,12 @@ static int pick_tile_by_shape(const ConvArgs& a) {
 
 int conv_pick_tile(const ConvArgs& a) {
     const int t = pick_tile_by_shape(a);
-    // hidden layers on the 64x64 and 128x128 tiles take the lean kernel
+    // unsplit reductions on the 64x64 and 128x128 tiles take the lean kernel
     // (its load streams keep 32-bit positions)
     const long long nkt = (long long)a.taps * (a.cin_pad / KT);
     const bool fits = nkt * a.n_pad * KT < (1LL << 32) && (long long)(a.cin_pad / KT) * a.in_plane < (1LL << 32);
-    if (pick_epi(a) == EPI_ANY || !fits) return t;
-    return t == kSmall ? kSmallLean : t == kMid ? kMidLean : t;
+    if (!fits || (t != kSmall && t != kMid) || conv_pick_splits(a, t) != 1) return t;
+    return t == kSmall ? kSmallLean : kMidLean;
 }
 
 // K splits for a layer whose tiles alone cannot fill the chip (only the general epilogue
