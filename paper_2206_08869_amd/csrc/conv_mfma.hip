@@ -755,7 +755,7 @@ __device__ __forceinline__ void wait_frags_then_barrier(v4i (&w)[NWF], v4i (&x)[
 // partial sums (integers: any order of addition gives the same result) meet once, through LDS, before the
 // epilogue, which group 0 runs. Unsplit reductions only.
 template <int BC, int BP, int WC, int WP, int KS, int EPI>
-__global__ __launch_bounds__(WC* WP* KS * 64) void conv_igemm_lean(const ConvArgs a, const int npb, const int ncb) {
+__global__ __launch_bounds__(WC* WP* KS * 64, KS) void conv_igemm_lean(const ConvArgs a, const int npb, const int ncb) {
     static_assert(KS == 1 || KS == 2, "a k-tile has two k-steps");
     constexpr int NST = 9;
     constexpr int NQ = WC * WP, NW = KS * NQ;
@@ -962,9 +962,12 @@ __global__ __launch_bounds__(WC* WP* KS * 64) void conv_igemm_lean(const ConvArg
         });
     });
     if constexpr (KS == 2) {
-        // group 1 hands its sums to group 0 through LDS (an area of its own: loads issued past the last
-        // k-tile may still be landing in the ring): 16 bytes per lane and register quad, lane-contiguous
-        unsigned char* const red = lds + NST * STAGE + CST + wq * (TC * TP * 4096) + lane * 16;
+        // group 1 hands its sums to group 0 through the ring's LDS, once the loads issued past the last
+        // k-tile have landed there for every wave (a workgroup then needs 74 KB and two share a CU):
+        // 16 bytes per lane and register quad, lane-contiguous
+        static_assert(NQ * TC * TP * 4096 <= NST * STAGE, "partial sums fit the ring");
+        asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+        unsigned char* const red = lds + wq * (TC * TP * 4096) + lane * 16;
         if (kh == 1) {
             static_for<TC>([&](auto tc_) {
                 constexpr int tc = decltype(tc_)::value;
@@ -1319,7 +1322,7 @@ const TileCfg kTiles[] = {
     IODF_TILE(128, 256, 2, 2, 3),
     // lean forms of the 64x64 tile (eight waves, the k-steps split between two groups of four) and of the
     // 128x128 tile for layers whose reduction is not split (see conv_igemm_lean)
-    TileCfg{64, 64, (size_t)9 * (64 + 64) * KT + 2048 + 4 * 4096,
+    TileCfg{64, 64, (size_t)9 * (64 + 64) * KT + 2048,
             {conv_igemm_lean<64, 64, 2, 2, 2, EPI_ANY>, conv_igemm_lean<64, 64, 2, 2, 2, EPI_FAST>, conv_igemm_lean<64, 64, 2, 2, 2, EPI_FAST_RELU>},
             512, "conv_igemm_lean<64,64,2,2,2>"},
     TileCfg{128, 128, (size_t)9 * (128 + 128) * KT + 2048,
@@ -1450,7 +1453,11 @@ int conv_pick_tile(const ConvArgs& a) {
     const long long nkt = (long long)a.taps * (a.cin_pad / KT);
     const bool fits = nkt * a.n_pad * KT < (1LL << 32) && (long long)(a.cin_pad / KT) * a.in_plane < (1LL << 32);
     if (!fits || (t != kSmall && t != kMid) || conv_pick_splits(a, t) != 1) return t;
-    return t == kSmall ? kSmallLean : kMidLean;
+    if (t == kSmall) return kSmallLean;
+    // the lean 128x128 form fills the LDS of a CU; with more tiles than CUs the four-stage form, two to a CU, is
+    // the better one (a second workgroup's loads and epilogue run under the first one's matrix work)
+    const long long blocks = (long long)((a.npix + 127) / 128) * ((a.n_store + 127) / 128);
+    return blocks <= a.n_cu ? kMidLean : t;
 }
 
 // K splits for a layer whose tiles alone cannot fill the chip (only the general epilogue
