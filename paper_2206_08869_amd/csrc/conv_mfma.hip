@@ -354,6 +354,36 @@ __device__ __forceinline__ void trace_stamp(const ConvArgs& a, int slot, int whi
     }
 }
 
+// Hand-placed LDS fragment reads (see conv_igemm_lean). The destination is an output of the read statement
+// and an in/out operand of the wait that covers it, so no use of it can be scheduled ahead of that wait.
+template <int OFF>
+__device__ __forceinline__ void lds_read_b128(v4i& d, const unsigned addr) {
+    static_assert(OFF >= 0 && OFF < 65536, "16-bit offset field");
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFF));
+}
+// Marks the fragments as produced here: what uses them stays behind every asm statement before this point.
+template <int NWF, int NAF>
+__device__ __forceinline__ void tie_frags(v4i (&w)[NWF], v4i (&x)[NAF]) {
+#pragma unroll
+    for (int i = 0; i < NWF; ++i) asm volatile("" : "+v"(w[i]));
+#pragma unroll
+    for (int i = 0; i < NAF; ++i) asm volatile("" : "+v"(x[i]));
+}
+// at most LG LDS operations of this wave outstanding; the fragments w, x are among the completed ones
+template <int LG, int NWF, int NAF>
+__device__ __forceinline__ void wait_frags(v4i (&w)[NWF], v4i (&x)[NAF]) {
+    static_assert(LG >= 0 && LG < 16, "counter width");
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(LG) : "memory");
+    tie_frags(w, x);
+}
+// at most VM vector-memory operations and LG LDS operations of this wave outstanding, then the barrier
+template <int VM, int LG, int NWF, int NAF>
+__device__ __forceinline__ void wait_frags_then_barrier(v4i (&w)[NWF], v4i (&x)[NAF]) {
+    static_assert(VM >= 0 && VM < 64 && LG >= 0 && LG < 16, "counter widths");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(%1)\n\ts_barrier" ::"n"(VM), "n"(LG) : "memory");
+    tie_frags(w, x);
+}
+
 // BC channels x BP pixels per workgroup, WC x WP waves, NST LDS stages of one 64-byte k-tile.
 //
 // Tiles go from global memory straight into LDS (global_load_lds_dwordx4): a wave-wide load
@@ -583,28 +613,63 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
     trace_stamp(a, bid, 1, tid);
     if (lean) {
         if constexpr (!SMALL) {
+            // Fragment reads and their waits are placed by hand, as in the persistent kernel: the second
+            // k-step's fragments are requested, the wait covers the first k-step's only, the MFMAs follow; after
+            // the barrier the other way round. (Left to the compiler, the first use of a fragment is preceded by
+            // lgkmcnt(0), which also waits for the reads issued just before it.) A ds_read offset has 16 bits:
+            // one base address per operand, k-step and group of G stages.
+            constexpr int G = 65536 / STAGE, NB = (NST + G - 1) / G;
+            constexpr int FR = TC + TP;
+            static_assert(G >= 1 && FR < 16, "stage size, counter width");
+            const unsigned ldsa = (unsigned)(unsigned long long)(lptr_t)lds;
+            unsigned wadr[2][NB], aadr[2][NB];
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    wadr[ks][b] = ldsa + b * G * STAGE + wl0 + (off0 ^ (ks * 32));
+                    aadr[ks][b] = ldsa + b * G * STAGE + al0 + (off0 ^ (ks * 32));
+                }
+            auto aread = [&](auto stage_, auto ks_, v4i (&wf)[TC], v4i (&af)[TP]) {
+                constexpr int stage = decltype(stage_)::value, ks = decltype(ks_)::value;
+                static_for<TC>([&](auto tc_) {
+                    constexpr int tc = decltype(tc_)::value;
+                    lds_read_b128<(stage % G) * STAGE + tc * 32 * KT>(wf[tc], wadr[ks][stage / G]);
+                });
+                static_for<TP>([&](auto tp_) {
+                    constexpr int tp = decltype(tp_)::value;
+                    lds_read_b128<(stage % G) * STAGE + tp * 32 * KT>(af[tp], aadr[ks][stage / G]);
+                });
+            };
             auto big_loop = [&](auto taps_) {
                 constexpr int taps = decltype(taps_)::value;
                 constexpr int U = taps == 1 ? NST : NST % 9 == 0 ? NST : NST % 3 == 0 ? 3 * NST : 9 * NST;  // lcm(NST, taps)
-                read_frags(0, 0, wf0, af0);
+                using I0 = std::integral_constant<int, 0>;
+                using I1 = std::integral_constant<int, 1>;
+                aread(I0{}, I0{}, wf0, af0);
                 for (int kt = 0; kt < nkt; kt += U) {
                     const int left = nkt - kt;
                     static_for<U>([&](auto i_) {
                         constexpr int i = decltype(i_)::value;
                         constexpr int st = i % NST;
                         if (left > i) {
-                            read_frags(st, 1, wf1, af1);
+                            aread(std::integral_constant<int, st>{}, I1{}, wf1, af1);
+                            wait_frags<FR>(wf0, af0);
                             mma(wf0, af0);
                             // everybody is past its reads of tile kt+i-1 (they returned before the last barrier), so
                             // its stage takes tile kt+i+NST-1; then wait until tile kt+i+1 has landed for everybody
                             lean_issue(std::integral_constant<int, (i + NST - 1) % NST>{},
                                        std::integral_constant<int, taps == 9 ? (i + NST - 1) % 9 : 0>{}, taps_);
                             wait_tiles_then_barrier<(NST - 2) * LPT>();
-                            read_frags((st + 1) % NST, 0, wf0, af0);
+                            tie_frags(wf1, af1);
+                            aread(std::integral_constant<int, (st + 1) % NST>{}, I0{}, wf0, af0);
                             mma(wf1, af1);
                         }
                     });
                 }
+                // the reads of the k-tile after the last one are still on their way to registers that the
+                // epilogue is free to use
+                wait_frags<0>(wf0, af0);
             };
             if (a.taps == 9) big_loop(std::integral_constant<int, 9>{});
             else big_loop(std::integral_constant<int, 1>{});
@@ -704,36 +769,6 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
     // before the wave retires and its LDS goes to another workgroup; they do so while the epilogue runs.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     trace_stamp(a, bid, 3, tid);
-}
-
-// Hand-placed LDS fragment reads (see conv_igemm_lean). The destination is an output of the read statement
-// and an in/out operand of the wait that covers it, so no use of it can be scheduled ahead of that wait.
-template <int OFF>
-__device__ __forceinline__ void lds_read_b128(v4i& d, const unsigned addr) {
-    static_assert(OFF >= 0 && OFF < 65536, "16-bit offset field");
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFF));
-}
-// Marks the fragments as produced here: what uses them stays behind every asm statement before this point.
-template <int NWF, int NAF>
-__device__ __forceinline__ void tie_frags(v4i (&w)[NWF], v4i (&x)[NAF]) {
-#pragma unroll
-    for (int i = 0; i < NWF; ++i) asm volatile("" : "+v"(w[i]));
-#pragma unroll
-    for (int i = 0; i < NAF; ++i) asm volatile("" : "+v"(x[i]));
-}
-// at most LG LDS operations of this wave outstanding; the fragments w, x are among the completed ones
-template <int LG, int NWF, int NAF>
-__device__ __forceinline__ void wait_frags(v4i (&w)[NWF], v4i (&x)[NAF]) {
-    static_assert(LG >= 0 && LG < 16, "counter width");
-    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(LG) : "memory");
-    tie_frags(w, x);
-}
-// at most VM vector-memory operations and LG LDS operations of this wave outstanding, then the barrier
-template <int VM, int LG, int NWF, int NAF>
-__device__ __forceinline__ void wait_frags_then_barrier(v4i (&w)[NWF], v4i (&x)[NAF]) {
-    static_assert(VM >= 0 && VM < 64 && LG >= 0 && LG < 16, "counter widths");
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(%1)\n\ts_barrier" ::"n"(VM), "n"(LG) : "memory");
-    tie_frags(w, x);
 }
 
 // Small and medium tiles, for launches with few pixels (the deep levels of a flow, everything at batch 1).
@@ -1405,12 +1440,14 @@ int pick_epi(const ConvArgs& a) {
     return !fast ? EPI_ANY : (a.relu && !a.shortcut && a.clamp_hi) ? EPI_FAST_RELU : fast_signed_ok ? EPI_FAST : EPI_ANY;
 }
 
-// Whether the 256x256 tile runs in its persistent form: two or more tiles per CU, a fast epilogue
-// and a k-tile count that is a whole number of the kernel's unrolled rounds (ring stages x taps).
+// Whether the 256x256 tile runs in its persistent form: a tile or more per CU, a fast epilogue and a k-tile
+// count that is a whole number of the kernel's unrolled rounds (ring stages x taps). With one tile per
+// workgroup nothing is left to overlap, but its branch-free k loop and its constants by DMA still make it
+// the faster form (2 % on 3x3 layers, 3-8 % on 1x1 layers).
 bool persist_ok(const ConvArgs& a, long long tiles) {
     const int nkt = a.taps * (a.cin_pad / KT);
     return pick_epi(a) != EPI_ANY && nkt % (a.taps == 9 ? 36 : 4) == 0 && persist_grid(a) >= 8 &&
-           tiles >= 2LL * persist_grid(a);
+           tiles >= (long long)persist_grid(a);
 }
 
 // First tile in table order that still fills the chip (its two-per-CU half when the reduction is
@@ -1499,7 +1536,7 @@ hipError_t launch_conv(const ConvArgs& a_in, hipStream_t stream) {
     const int grid = ((npb + 7) / 8) * 8 * ncb;
     const int epi = pick_epi(a);
     const int splits = conv_pick_splits(a, best);
-    // Two or more tiles per CU, a fast epilogue and whole rounds of the stage ring: one resident
+    // A tile or more per CU, a fast epilogue and whole rounds of the stage ring: one resident
     // workgroup per CU walks its tiles and overlaps each tile's first loads with the epilogue before it.
     if (persist) {
         hipLaunchKernelGGL(kPersist[epi], dim3(persist_grid(a)), dim3(t.threads), kPersistLds, stream, a, npb, ncb);

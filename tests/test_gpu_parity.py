@@ -237,7 +237,7 @@ def test_single_convolution_matches_oracle(c_in, c_out, k, relu, shift_lo):
     (2048, 512, 1, 96, 32),   # 32 k-tiles, 768 tiles: the persistent form of the 256x256 tile
     (256, 512, 3, 97, 32),    # 3x3, 36 k-tiles, 776 tiles: persistent, workgroups with three and with four tiles
     (1280, 256, 1, 219, 30),  # persistent, one channel block, 197100 pixels (ragged), sides that are no powers of two
-    (1280, 256, 1, 92, 30),   # the same layer on 324 tiles (1.3 per CU): too few for the persistent form
+    (1280, 256, 1, 92, 30),   # the same layer on 324 tiles (1.3 per CU): workgroups with one and with two tiles
     (512, 512, 1, 92, 30),    # 82800 pixels: a ragged last half tile, image sides that are no powers of two
     (128, 128, 3, 183, 30),   # 164700 pixels, ragged, 3x3
 ])
