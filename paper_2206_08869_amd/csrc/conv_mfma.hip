@@ -613,63 +613,28 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
     trace_stamp(a, bid, 1, tid);
     if (lean) {
         if constexpr (!SMALL) {
-            // Fragment reads and their waits are placed by hand, as in the persistent kernel: the second
-            // k-step's fragments are requested, the wait covers the first k-step's only, the MFMAs follow; after
-            // the barrier the other way round. (Left to the compiler, the first use of a fragment is preceded by
-            // lgkmcnt(0), which also waits for the reads issued just before it.) A ds_read offset has 16 bits:
-            // one base address per operand, k-step and group of G stages.
-            constexpr int G = 65536 / STAGE, NB = (NST + G - 1) / G;
-            constexpr int FR = TC + TP;
-            static_assert(G >= 1 && FR < 16, "stage size, counter width");
-            const unsigned ldsa = (unsigned)(unsigned long long)(lptr_t)lds;
-            unsigned wadr[2][NB], aadr[2][NB];
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                for (int b = 0; b < NB; ++b) {
-                    wadr[ks][b] = ldsa + b * G * STAGE + wl0 + (off0 ^ (ks * 32));
-                    aadr[ks][b] = ldsa + b * G * STAGE + al0 + (off0 ^ (ks * 32));
-                }
-            auto aread = [&](auto stage_, auto ks_, v4i (&wf)[TC], v4i (&af)[TP]) {
-                constexpr int stage = decltype(stage_)::value, ks = decltype(ks_)::value;
-                static_for<TC>([&](auto tc_) {
-                    constexpr int tc = decltype(tc_)::value;
-                    lds_read_b128<(stage % G) * STAGE + tc * 32 * KT>(wf[tc], wadr[ks][stage / G]);
-                });
-                static_for<TP>([&](auto tp_) {
-                    constexpr int tp = decltype(tp_)::value;
-                    lds_read_b128<(stage % G) * STAGE + tp * 32 * KT>(af[tp], aadr[ks][stage / G]);
-                });
-            };
             auto big_loop = [&](auto taps_) {
                 constexpr int taps = decltype(taps_)::value;
                 constexpr int U = taps == 1 ? NST : NST % 9 == 0 ? NST : NST % 3 == 0 ? 3 * NST : 9 * NST;  // lcm(NST, taps)
-                using I0 = std::integral_constant<int, 0>;
-                using I1 = std::integral_constant<int, 1>;
-                aread(I0{}, I0{}, wf0, af0);
+                read_frags(0, 0, wf0, af0);
                 for (int kt = 0; kt < nkt; kt += U) {
                     const int left = nkt - kt;
                     static_for<U>([&](auto i_) {
                         constexpr int i = decltype(i_)::value;
                         constexpr int st = i % NST;
                         if (left > i) {
-                            aread(std::integral_constant<int, st>{}, I1{}, wf1, af1);
-                            wait_frags<FR>(wf0, af0);
+                            read_frags(st, 1, wf1, af1);
                             mma(wf0, af0);
                             // everybody is past its reads of tile kt+i-1 (they returned before the last barrier), so
                             // its stage takes tile kt+i+NST-1; then wait until tile kt+i+1 has landed for everybody
                             lean_issue(std::integral_constant<int, (i + NST - 1) % NST>{},
                                        std::integral_constant<int, taps == 9 ? (i + NST - 1) % 9 : 0>{}, taps_);
                             wait_tiles_then_barrier<(NST - 2) * LPT>();
-                            tie_frags(wf1, af1);
-                            aread(std::integral_constant<int, (st + 1) % NST>{}, I0{}, wf0, af0);
+                            read_frags((st + 1) % NST, 0, wf0, af0);
                             mma(wf1, af1);
                         }
                     });
                 }
-                // the reads of the k-tile after the last one are still on their way to registers that the
-                // epilogue is free to use
-                wait_frags<0>(wf0, af0);
             };
             if (a.taps == 9) big_loop(std::integral_constant<int, 9>{});
             else big_loop(std::integral_constant<int, 1>{});
