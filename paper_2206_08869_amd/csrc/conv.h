@@ -69,6 +69,11 @@ struct ConvArgs {
     // tile start and end. Slots are numbered as blockIdx.x of the plain kernel numbers them.
     long long* trace;
     int n_cu;      // compute units of the device the layer runs on (conv_device_cus); decides the launch shape
+    // Optional: memory the next launch will read first (its packed weights). A launch with a handful of tiles
+    // adds a few workgroups that touch it, one load per cache line, so that it sits in the L2 of the XCDs
+    // that hold tiles when that launch starts.
+    const int8_t* pf;
+    long long pf_bytes;
     int log2_w, log2_hw;  // filled by launch_conv: log2 of w and of h*w when both are powers of two, else -1
     int32_t* partial;  // optional split-K scratch: int32 [npix][n_pad], all zero between launches
     int n_store;   // channels written (<= n_pad); multiple of 4 in MODE_ACT

@@ -781,6 +781,16 @@ __global__ __launch_bounds__(WC* WP* KS * 64, KS) void conv_igemm_lean(const Con
 
     const int bid = blockIdx.x;
     const int xcd = bid & 7, slot = bid >> 3;
+    const int tile_grid = ((npb + 7) / 8) * 8 * ncb;
+    if (bid >= tile_grid) {
+        // workgroups beyond the tiles (see ConvArgs::pf): those on an XCD that holds tiles share the lines
+        if (xcd >= npb) return;
+        const int j = (bid - tile_grid) >> 3, P = ((int)gridDim.x - tile_grid) >> 3;
+        const long long lines = (a.pf_bytes + 127) >> 7;
+        for (long long l = (long long)j * blockDim.x + tid; l < lines; l += (long long)P * blockDim.x)
+            (void)*(const volatile int*)(a.pf + (l << 7));
+        return;
+    }
     const int pb = (slot / ncb) * 8 + xcd, cb = slot % ncb;
     if (pb >= npb) return;
     const int p0 = pb * BP, c0 = cb * BC;
@@ -1507,7 +1517,10 @@ hipError_t launch_conv(const ConvArgs& a_in, hipStream_t stream) {
         hipLaunchKernelGGL(kPersist[epi], dim3(persist_grid(a)), dim3(t.threads), kPersistLds, stream, a, npb, ncb);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(t.kern[epi], dim3(grid, splits), dim3(t.threads), t.lds, stream, a, npb, ncb);
+    // few tiles, and the next launch's first reads known: four more workgroups per XCD fetch them (lean kernel only)
+    const bool lean_tile = best == kSmallLean || best == kMidLean;
+    const int pf_grid = lean_tile && a.pf && a.pf_bytes > 0 && (long long)npb * ncb <= 64 ? 32 : 0;
+    hipLaunchKernelGGL(t.kern[epi], dim3(grid + pf_grid, splits), dim3(t.threads), t.lds, stream, a, npb, ncb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits == 1) return e;
     const long long n = (long long)a.npix * a.n_store;

@@ -609,7 +609,21 @@ long long issued_macs(const ConvArgs& a) {
 
 static const int32_t* partial_of(const iodf_ctx* ctx);
 
-int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* codes, hipStream_t st) {
+// What a layer's launch reads first: its packed weights and, behind them in the parameter buffer, its
+// per-channel constants.
+static void layer_param_span(const iodf_ctx* ctx, const DevLayer& L, const int8_t** p, long long* bytes) {
+    size_t end = L.shift_off + 4 * (size_t)L.n_pad;
+    if (L.hi_off != (size_t)-1) end = std::max(end, L.hi_off + 4 * (size_t)L.n_pad);
+    if (L.mode == MODE_RAW) end = std::max(end, L.fin_shift_off + 4 * (size_t)L.expand_c_out);
+    const size_t wbytes = (size_t)L.taps * L.cin_pad * L.n_pad;
+    if (end <= L.wgt_off || end > ctx->params_bytes || end - L.wgt_off > wbytes + (1u << 20)) end = L.wgt_off + wbytes;
+    *p = (const int8_t*)(ctx->params + L.wgt_off);
+    *bytes = (long long)(end - L.wgt_off);
+}
+
+// `next`: the network that runs after this one (its first layer's parameters are prefetched), or nullptr.
+int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* codes, hipStream_t st,
+            const DevNet* next = nullptr) {
     const int lv = N.level;
     const int h = ctx->shape.H >> lv, w = ctx->shape.W >> lv;
     const int npix = batch * h * w;
@@ -618,9 +632,12 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
     PROF_LAUNCH(ctx, st, CLS_QUANT_IN, 0, (long long)npix * (4 * N.C_in + (N.C_in + 3) / 4 * 4),
                 launch_quant_in(ctx->state[lv], npix, h, w, N.C, phi, N.C_in, N.M_in, N.s_in, ctx->buf[lv][BUF_XQ],
                                 N.cin_pad0, plane, st));
-    for (const DevLayer& L : N.layers) {
+    for (size_t li = 0; li < N.layers.size(); ++li) {
+        const DevLayer& L = N.layers[li];
         ConvArgs a;
         memset(&a, 0, sizeof(a));
+        if (li + 1 < N.layers.size()) layer_param_span(ctx, N.layers[li + 1], &a.pf, &a.pf_bytes);
+        else if (next && !next->layers.empty()) layer_param_span(ctx, next->layers[0], &a.pf, &a.pf_bytes);
         a.in = ctx->buf[lv][L.in_buf];
         a.in_plane = plane;
         a.in_chunk0 = L.in_off / 64;
@@ -920,17 +937,20 @@ static int enqueue_forward(iodf_ctx* ctx, const uint8_t* x_dev, int batch, int32
     for (int lv = 1; lv <= m.levels; ++lv) {
         const int C = level_channels(lv), h = m.H >> lv, w = m.W >> lv;
         const int n0 = ctx->first_net[lv];
+        const bool last = lv == m.levels;
+        const bool head = !last && m.has_heads && codes_dev;
+        const DevNet* const after_level = last ? nullptr : &ctx->nets[ctx->first_net[lv + 1]];
         for (int k = 0; k < m.couplings; ++k) {
-            const int rc = run_net(ctx, ctx->nets[n0 + k], batch, +1, nullptr, st);
+            const DevNet* next = k + 1 < m.couplings ? &ctx->nets[n0 + k + 1] : head ? &ctx->nets[n0 + m.couplings] : after_level;
+            const int rc = run_net(ctx, ctx->nets[n0 + k], batch, +1, nullptr, st, next);
             if (rc != IODF_OK) return rc;
         }
         const int32_t* phi = (const int32_t*)(ctx->params + ctx->nets[n0 + m.couplings - 1].phi_off);
-        const bool last = lv == m.levels;
         PROF_LAUNCH(ctx, st, CLS_FACTOR_OUT, 0, 8LL * batch * C * h * w,
                     launch_factor_out(ctx->state[lv], batch, h, w, C, phi, last ? 0 : C / 2, z_dev, ctx->d,
                                       ctx->z_off[lv], last ? nullptr : ctx->state[lv + 1], st));
-        if (!last && m.has_heads && codes_dev) {
-            const int rc = run_net(ctx, ctx->nets[n0 + m.couplings], batch, +1, codes_dev, st);
+        if (head) {
+            const int rc = run_net(ctx, ctx->nets[n0 + m.couplings], batch, +1, codes_dev, st, after_level);
             if (rc != IODF_OK) return rc;
         }
     }
@@ -948,7 +968,8 @@ static int enqueue_inverse(iodf_ctx* ctx, const int32_t* z_dev, int batch, uint8
                     launch_unfactor(ctx->state[lv], batch, h, w, C, phi, last ? 0 : C / 2, z_dev, ctx->d,
                                     ctx->z_off[lv], last ? nullptr : ctx->state[lv + 1], st));
         for (int k = m.couplings - 1; k >= 0; --k) {
-            const int rc = run_net(ctx, ctx->nets[n0 + k], batch, -1, nullptr, st);
+            const DevNet* next = k > 0 ? &ctx->nets[n0 + k - 1] : lv > 1 ? &ctx->nets[ctx->first_net[lv - 1] + m.couplings - 1] : nullptr;
+            const int rc = run_net(ctx, ctx->nets[n0 + k], batch, -1, nullptr, st, next);
             if (rc != IODF_OK) return rc;
         }
     }
