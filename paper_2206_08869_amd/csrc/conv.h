@@ -51,12 +51,10 @@ struct ConvArgs {
     // weights: int8 [cin_pad / 64][taps][n_pad][64]: k-tile major (64-channel plane, then tap), so a
     // [channels][64] tile is contiguous and the taps of one plane follow each other
     const int8_t* wgt;
-    int n_pad;     // multiple of 64; rows n >= true C_out are zero
     // per output channel constants, length n_pad
     const int32_t* bias;
     const int32_t* mul;
     const int32_t* shift;  // rq_fast: shift - 32 (every shift of the layer is >= 33); else the shift itself
-    int rq_fast;
     // rq_fast only: smallest accumulator (bias included) whose requantised value reaches the top code
     // (127, or 255 with out_unsigned), saturated to INT32_MAX; lets a ReLU layer clamp before the multiply instead of after it
     const int32_t* clamp_hi;
@@ -68,7 +66,6 @@ struct ConvArgs {
     // first k-tile landed, after the k loop and after the epilogue; [4], [5] = the shader-clock counter at
     // tile start and end. Slots are numbered as blockIdx.x of the plain kernel numbers them.
     long long* trace;
-    int n_cu;      // compute units of the device the layer runs on (conv_device_cus); decides the launch shape
     // Optional: memory the next launch will read first (its packed weights). A launch with a handful of tiles
     // adds a few workgroups that touch it, one load per cache line, so that it sits in the L2 of the XCDs
     // that hold tiles when that launch starts.
@@ -78,21 +75,31 @@ struct ConvArgs {
     int32_t* partial;  // optional split-K scratch: int32 [npix][n_pad], all zero between launches
     int n_store;   // channels written (<= n_pad); multiple of 4 in MODE_ACT
     int mode;
+    // What the epilogue writes depends on the mode, and only that mode's fields are read: they share storage.
+    union {
+        struct {  // MODE_ACT
+            int8_t* out;
+            long long out_plane;
+            int out_chunk0;
+            int shortcut;            // add the 8-bit code already stored at the output location
+        };
+        struct {  // MODE_COUPLE
+            int32_t* state;          // int32 pixel-major [npix][state_c]
+            const int32_t* idx_b;    // physical channel of translation channel n
+        };
+        struct {  // MODE_CODES
+            int8_t* codes;           // image b, channel n, pixel q at codes[b * codes_img_stride + codes_off + n * h*w + q]
+            long long codes_img_stride;
+            long long codes_off;
+        };
+    };
+    // (the 4-byte fields without a partner sit together so that the argument block has no holes)
+    int n_pad;     // multiple of 64; rows n >= true C_out are zero
+    int rq_fast;
+    int n_cu;      // compute units of the device the layer runs on (conv_device_cus); decides the launch shape
     int relu;
-    // MODE_ACT
-    int8_t* out;
-    long long out_plane;
-    int out_chunk0;
-    int shortcut;            // add the 8-bit code already stored at the output location
-    // MODE_COUPLE
-    int32_t* state;          // int32 pixel-major [npix][state_c]
     int state_c;
-    const int32_t* idx_b;    // physical channel of translation channel n
     int sign;                // +1 encode, -1 decode
-    // MODE_CODES
-    int8_t* codes;           // image b, channel n, pixel q at codes[b * codes_img_stride + codes_off + n * h*w + q]
-    long long codes_img_stride;
-    long long codes_off;
 };
 
 // Enqueue the layer on `stream`. Returns hipSuccess or the launch error.
