@@ -347,7 +347,7 @@ __device__ __forceinline__ void wait_tiles_then_barrier() {
 
 // Timeline of one output tile (see ConvArgs::trace): stamp `which` of slot `slot`.
 __device__ __forceinline__ void trace_stamp(const ConvArgs& a, int slot, int which, int tid) {
-    if (a.trace && tid == 0) {
+    if (a.has_trace && tid == 0) {
         a.trace[8LL * slot + which] = (long long)wall_clock64();
         if (which == 0) a.trace[8LL * slot + 4] = (long long)clock64();
         if (which == 3) a.trace[8LL * slot + 5] = (long long)clock64();
@@ -398,7 +398,8 @@ __device__ __forceinline__ void wait_frags_then_barrier(v4i (&w)[NWF], v4i (&x)[
 // per-tile address arithmetic is scalar, the per-lane parts are computed once.
 // Four-wave, three-stage configurations are compiled for two workgroups per CU.
 template <int BC, int BP, int WC, int WP, int NST, int EPI>
-__global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) void conv_igemm(const ConvArgs a, const int npb, const int ncb) {
+__global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) void conv_igemm(const ConvArgs a) {
+    const int npb = (a.npix + BP - 1) / BP, ncb = a.n_pad / BC;  // pixel blocks, channel blocks
     constexpr int NW = WC * WP;
     constexpr int WTC = BC / WC, WTP = BP / WP;  // wave tile
     constexpr int TC = WTC / 32, TP = WTP / 32;  // 32x32 MFMA tiles per wave
@@ -755,7 +756,8 @@ __global__ __launch_bounds__(WC* WP * 64, (WC * WP == 4 && NST == 3) ? 2 : 1) vo
 // partial sums (integers: any order of addition gives the same result) meet once, through LDS, before the
 // epilogue, which group 0 runs. Unsplit reductions only.
 template <int BC, int BP, int WC, int WP, int KS, int EPI>
-__global__ __launch_bounds__(WC* WP* KS * 64, KS) void conv_igemm_lean(const ConvArgs a, const int npb, const int ncb) {
+__global__ __launch_bounds__(WC* WP* KS * 64, KS) void conv_igemm_lean(const ConvArgs a) {
+    const int npb = (a.npix + BP - 1) / BP, ncb = a.n_pad / BC;  // pixel blocks, channel blocks
     static_assert(KS == 1 || KS == 2, "a k-tile has two k-steps");
     constexpr int NST = 9;
     constexpr int NQ = WC * WP, NW = KS * NQ;
@@ -1036,7 +1038,8 @@ __global__ __launch_bounds__(WC* WP* KS * 64, KS) void conv_igemm_lean(const Con
 // as the tiles: four 1 KB loads straight into one of two LDS buffers, issued right behind the last
 // k-tile of the previous output tile, so they too are older than the next tile's k-tile 0.
 template <int BC, int BP, int WC, int WP, int NST, int EPI>
-__global__ __launch_bounds__(WC* WP * 64) void conv_igemm_persist(const ConvArgs a, const int npb, const int ncb) {
+__global__ __launch_bounds__(WC* WP * 64) void conv_igemm_persist(const ConvArgs a) {
+    const int npb = (a.npix + BP - 1) / BP, ncb = a.n_pad / BC;  // pixel blocks, channel blocks
     static_assert(EPI != EPI_ANY, "fast epilogues only");
     static_assert(BC == 256 && WC * WP >= 4, "one wave-wide load per constant array");
     constexpr int NW = WC * WP;
@@ -1306,7 +1309,7 @@ namespace {
 struct TileCfg {
     int bc, bp;
     size_t lds;
-    void (*kern[3])(const ConvArgs, int, int);  // indexed by EPI_*
+    void (*kern[3])(const ConvArgs);  // indexed by EPI_*
     int threads;
     const char* name;
 };
@@ -1344,7 +1347,7 @@ constexpr int kPair256 = 5, kPair128 = 6;  // the two-workgroups-per-CU halves o
 constexpr int kSmall = 4, kSmallLean = 7, kMid = 2, kMidLean = 8;  // the 64x64 and 128x128 tiles and their lean forms
 
 // Persistent form of tile 0 (see conv_igemm_persist), by fast epilogue, and its LDS bytes.
-void (*const kPersist[3])(const ConvArgs, int, int) = {nullptr, conv_igemm_persist<256, 256, 2, 4, 4, EPI_FAST>,
+void (*const kPersist[3])(const ConvArgs) = {nullptr, conv_igemm_persist<256, 256, 2, 4, 4, EPI_FAST>,
                                                         conv_igemm_persist<256, 256, 2, 4, 4, EPI_FAST_RELU>};
 constexpr size_t kPersistLds = (size_t)4 * (256 + 256) * KT + 2 * 4 * 256 * sizeof(int);
 constexpr int kPersistTile = kNumTiles;  // what conv_pick_tile answers for a persistent launch of tile 0
@@ -1356,15 +1359,14 @@ int persist_grid(const ConvArgs& a) { return a.n_cu / 8 * 8; }
 bool args_ok(const ConvArgs& a) {
     return !(a.cin_pad <= 0 || a.cin_pad % KT || a.n_pad <= 0 || a.n_pad % 64 || (a.taps != 1 && a.taps != 9) ||
              a.in_plane < (long long)(a.npix / (a.h * a.w)) * (a.h + 2) * (a.w + 2) * KT || a.in_plane % 1024 ||
-             a.in_plane >= (1LL << 31) || a.in_chunk0 < 0 || a.n_store > a.n_pad ||
+             a.in_plane >= (1u << 31) || a.n_store > a.n_pad ||
              a.n_store < 1 || a.h < 1 || a.w < 1 || a.npix % (a.h * a.w) || !a.in || !a.wgt || !a.bias || !a.mul ||
              !a.shift ||
              (a.mode == MODE_ACT &&
               (!a.out || a.out_plane < (long long)(a.npix / (a.h * a.w)) * (a.h + 2) * (a.w + 2) * KT ||
-               a.out_plane % 64 || a.out_chunk0 < 0)) ||
+               a.out_plane % 64)) ||
              (a.mode == MODE_COUPLE && (!a.state || !a.idx_b || a.state_c < 1)) ||
-             (a.mode == MODE_CODES && !a.codes) || (a.mode == MODE_RAW && !a.partial) || a.mode < MODE_ACT ||
-             a.mode > MODE_RAW);
+             (a.mode == MODE_CODES && !a.codes) || (a.mode == MODE_RAW && !a.partial) || a.mode > MODE_RAW);
 }
 
 }  // namespace
@@ -1514,13 +1516,13 @@ hipError_t launch_conv(const ConvArgs& a_in, hipStream_t stream) {
     // A tile or more per CU, a fast epilogue and whole rounds of the stage ring: one resident
     // workgroup per CU walks its tiles and overlaps each tile's first loads with the epilogue before it.
     if (persist) {
-        hipLaunchKernelGGL(kPersist[epi], dim3(persist_grid(a)), dim3(t.threads), kPersistLds, stream, a, npb, ncb);
+        hipLaunchKernelGGL(kPersist[epi], dim3(persist_grid(a)), dim3(t.threads), kPersistLds, stream, a);
         return hipGetLastError();
     }
     // few tiles, and the next launch's first reads known: four more workgroups per XCD fetch them (lean kernel only)
     const bool lean_tile = best == kSmallLean || best == kMidLean;
-    const int pf_grid = lean_tile && a.pf && a.pf_bytes > 0 && (long long)npb * ncb <= 64 ? 32 : 0;
-    hipLaunchKernelGGL(t.kern[epi], dim3(grid + pf_grid, splits), dim3(t.threads), t.lds, stream, a, npb, ncb);
+    const int pf_grid = lean_tile && !a.has_trace && a.pf && a.pf_bytes > 0 && (long long)npb * ncb <= 64 ? 32 : 0;
+    hipLaunchKernelGGL(t.kern[epi], dim3(grid + pf_grid, splits), dim3(t.threads), t.lds, stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits == 1) return e;
     const long long n = (long long)a.npix * a.n_store;

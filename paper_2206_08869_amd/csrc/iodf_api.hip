@@ -611,14 +611,14 @@ static const int32_t* partial_of(const iodf_ctx* ctx);
 
 // What a layer's launch reads first: its packed weights and, behind them in the parameter buffer, its
 // per-channel constants.
-static void layer_param_span(const iodf_ctx* ctx, const DevLayer& L, const int8_t** p, long long* bytes) {
+static void layer_param_span(const iodf_ctx* ctx, const DevLayer& L, const int8_t** p, unsigned* bytes) {
     size_t end = L.shift_off + 4 * (size_t)L.n_pad;
     if (L.hi_off != (size_t)-1) end = std::max(end, L.hi_off + 4 * (size_t)L.n_pad);
     if (L.mode == MODE_RAW) end = std::max(end, L.fin_shift_off + 4 * (size_t)L.expand_c_out);
     const size_t wbytes = (size_t)L.taps * L.cin_pad * L.n_pad;
     if (end <= L.wgt_off || end > ctx->params_bytes || end - L.wgt_off > wbytes + (1u << 20)) end = L.wgt_off + wbytes;
     *p = (const int8_t*)(ctx->params + L.wgt_off);
-    *bytes = (long long)(end - L.wgt_off);
+    *bytes = (unsigned)std::min<size_t>(end - L.wgt_off, 0xffffffffu);
 }
 
 // `next`: the network that runs after this one (its first layer's parameters are prefetched), or nullptr.
@@ -636,8 +636,12 @@ int run_net(iodf_ctx* ctx, const DevNet& N, int batch, int mode_sign, int8_t* co
         const DevLayer& L = N.layers[li];
         ConvArgs a;
         memset(&a, 0, sizeof(a));
-        if (li + 1 < N.layers.size()) layer_param_span(ctx, N.layers[li + 1], &a.pf, &a.pf_bytes);
-        else if (next && !next->layers.empty()) layer_param_span(ctx, next->layers[0], &a.pf, &a.pf_bytes);
+        {
+            const DevLayer* Ln = li + 1 < N.layers.size() ? &N.layers[li + 1] : next && !next->layers.empty() ? &next->layers[0] : nullptr;
+            unsigned pfb = 0;
+            if (Ln) layer_param_span(ctx, *Ln, &a.pf, &pfb);
+            a.pf_bytes = pfb;
+        }
         a.in = ctx->buf[lv][L.in_buf];
         a.in_plane = plane;
         a.in_chunk0 = L.in_off / 64;
@@ -1415,8 +1419,10 @@ static int conv_probe_impl(int device_ordinal, int c_in, int c_out, int k, int h
         PROBE_TRY(hipMemset(dtrace, 0, 64 * (size_t)slots));
         for (int i = 0; i < iters; ++i) PROBE_TRY(launch_conv(a, nullptr));
         a.trace = dtrace;
+        a.has_trace = 1;
         PROBE_TRY(launch_conv(a, nullptr));
         a.trace = nullptr;
+        a.has_trace = 0;
         PROBE_TRY(hipDeviceSynchronize());
         std::vector<long long> tl(8 * (size_t)slots);
         PROBE_TRY(hipMemcpy(tl.data(), dtrace, 64 * (size_t)slots, hipMemcpyDeviceToHost));
