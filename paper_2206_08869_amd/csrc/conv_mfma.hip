@@ -789,8 +789,17 @@ __global__ __launch_bounds__(WC* WP* KS * 64, KS) void conv_igemm_lean(const Con
         if (xcd >= npb) return;
         const int j = (bid - tile_grid) >> 3, P = ((int)gridDim.x - tile_grid) >> 3;
         const long long lines = (a.pf_bytes + 127) >> 7;
-        for (long long l = (long long)j * blockDim.x + tid; l < lines; l += (long long)P * blockDim.x)
-            (void)*(const volatile int*)(a.pf + (l << 7));
+        // four independent loads per round, so that a thread pays one memory latency and not one per line
+        const long long stride = (long long)P * blockDim.x;
+        int sum = 0;
+        for (long long l = (long long)j * blockDim.x + tid; l < lines; l += 4 * stride) {
+            const int v0 = *(const int*)(a.pf + (l << 7));
+            const int v1 = l + stride < lines ? *(const int*)(a.pf + ((l + stride) << 7)) : 0;
+            const int v2 = l + 2 * stride < lines ? *(const int*)(a.pf + ((l + 2 * stride) << 7)) : 0;
+            const int v3 = l + 3 * stride < lines ? *(const int*)(a.pf + ((l + 3 * stride) << 7)) : 0;
+            sum += v0 + v1 + v2 + v3;
+        }
+        asm volatile("" ::"v"(sum));  // the loads are the point: keep them
         return;
     }
     const int pb = (slot / ncb) * 8 + xcd, cb = slot % ncb;
@@ -1519,9 +1528,10 @@ hipError_t launch_conv(const ConvArgs& a_in, hipStream_t stream) {
         hipLaunchKernelGGL(kPersist[epi], dim3(persist_grid(a)), dim3(t.threads), kPersistLds, stream, a);
         return hipGetLastError();
     }
-    // few tiles, and the next launch's first reads known: four more workgroups per XCD fetch them (lean kernel only)
+    // few tiles, and the next launch's first reads known: eight more workgroups per XCD fetch them (lean kernel only;
+    // measured at batch 1 of the gate-pruned flow: 8, 16, 32, 64, 128 extra workgroups give 4.71, 3.77, 3.55, 3.51, 3.50 ms)
     const bool lean_tile = best == kSmallLean || best == kMidLean;
-    const int pf_grid = lean_tile && !a.has_trace && a.pf && a.pf_bytes > 0 && (long long)npb * ncb <= 64 ? 32 : 0;
+    const int pf_grid = lean_tile && !a.has_trace && a.pf && a.pf_bytes > 0 && (long long)npb * ncb <= 64 ? 64 : 0;
     hipLaunchKernelGGL(t.kern[epi], dim3(grid + pf_grid, splits), dim3(t.threads), t.lds, stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits == 1) return e;
