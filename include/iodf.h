@@ -193,6 +193,7 @@ int iodf_untile_patches(iodf_ctx* ctx, const uint8_t* x_dev, int first_patch, in
  * The layer is packed and run exactly as inside a flow (same kernels, zero padding (k-1)/2); the
  * call allocates and frees its own device buffers, runs the layer once for y and then `iters` more
  * times between two events: *us_per_call (may be NULL) is the mean device time of one launch.
+ * k is 1 or 3; h, w <= 8192; c_in, c_out <= 65536; anything else is IODF_E_ARG.
  * Measurement support, not part of the coding path.
  */
 int iodf_conv_probe(int device_ordinal, int c_in, int c_out, int k, int h, int w, int batch, int relu,

@@ -1335,7 +1335,7 @@ static int conv_probe_impl(int device_ordinal, int c_in, int c_out, int k, int h
                            const uint8_t* shift_host, int8_t* y_host, int iters, float* us_per_call,
                            int64_t* timeline_host, int max_tiles, int* n_tiles) {
     if (timeline_host && (max_tiles < 1 || !n_tiles)) return IODF_E_ARG;
-    if (c_in < 1 || c_out < 1 || (k != 1 && k != 3) || h < 1 || w < 1 || batch < 1 || c_in > 65536 || c_out > 65536 ||
+    if (c_in < 1 || c_out < 1 || (k != 1 && k != 3) || h < 1 || w < 1 || h > 8192 || w > 8192 || batch < 1 || c_in > 65536 || c_out > 65536 ||
         !x_host || !w_host || !bias_host || !m_host || !shift_host || !y_host || iters < 1)
         return IODF_E_ARG;
     for (int c = 0; c < c_out; ++c)
