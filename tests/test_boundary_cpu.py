@@ -124,4 +124,9 @@ def test_codec_tables_of_the_library_are_the_correctly_rounded_ones():
     # the single-layer probe checks its arguments before it touches the device
     assert lib.iodf_conv_probe(0, 0, 8, 3, 4, 4, 1, 1, None, None, None, None, None, None, 1, None) == -1
     assert lib.iodf_conv_probe(0, 8, 8, 2, 4, 4, 1, 1, None, None, None, None, None, None, 1, None) == -1
+    # image sides beyond 8192 do not fit the kernels' argument block
+    import ctypes
+    buf = (ctypes.c_byte * 64)()
+    assert lib.iodf_conv_probe(0, 8, 8, 3, 8193, 4, 1, 1, buf, buf, buf, buf, buf, buf, 1, None) == -1
+    assert lib.iodf_conv_probe(0, 8, 8, 3, 4, 70000, 1, 1, buf, buf, buf, buf, buf, buf, 1, None) == -1
     assert lib.iodf_tile_patches(None, None, 8, 8, 0, 1, None, None) == -1
