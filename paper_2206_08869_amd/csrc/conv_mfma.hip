@@ -1549,6 +1549,15 @@ __global__ void conv_tapsum(const TapSumArgs a) {
     for (long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x; t < n; t += (long long)gridDim.x * blockDim.x) {
         const int m = (int)(t / a.c_out), c = (int)(t - (long long)m * a.c_out);
         const int b = m / hw, q = m - b * hw, i = q / a.w, j = q - i * a.w;
+        // the state word this thread updates: its address hangs on the channel map, so both loads start
+        // before the taps are summed rather than behind them
+        int32_t* sp = nullptr;
+        int sv = 0;
+        const int mul = a.mul[c], shift = a.shift[c];
+        if (a.mode == MODE_COUPLE) {
+            sp = a.state + (long long)m * a.state_c + a.idx_b[c];
+            sv = *sp;
+        }
         int acc = a.bias[c];
 #pragma unroll
         for (int tap = 0; tap < 9; ++tap) {
@@ -1556,11 +1565,11 @@ __global__ void conv_tapsum(const TapSumArgs a) {
             if (ii >= 0 && ii < a.h && jj >= 0 && jj < a.w)
                 acc += a.y[((long long)b * hw + ii * a.w + jj) * a.n_pad + tap * a.c_out + c];
         }
-        int y = rq_dev(acc, a.mul[c], a.shift[c]);
+        int y = rq_dev(acc, mul, shift);
         if (a.relu) y = y < 0 ? 0 : y;
         y = sat8_dev(y);
         if (a.mode == MODE_COUPLE)
-            a.state[(long long)m * a.state_c + a.idx_b[c]] += a.sign * y;
+            *sp = sv + a.sign * y;
         else
             a.codes[(long long)b * a.codes_img_stride + a.codes_off + (long long)c * hw + q] = (int8_t)y;
     }
